@@ -1,0 +1,159 @@
+/*
+ * attn.h -- C ABI of the MI355X (gfx950) exact-attention library.
+ *
+ * The library computes, for B*H independent problems of N tokens and head
+ * dimension d (paper: Section 2.2 and Appendix B.3),
+ *
+ *     S = tau * Q K^T,  S_masked = MASK(S),  P = softmax(S_masked) row-wise,
+ *     P_dropped = dropout(P, p_drop),        O = P_dropped V,
+ *
+ * without ever writing S or P to memory (tiling with an online softmax,
+ * Section 3.1 / Algorithm 1 and 2), and the gradients dQ, dK, dV of a scalar
+ * loss given dO by recomputing S and P tile by tile from Q, K, V and the saved
+ * per-row statistic (Appendix B.2 and B.4 / Algorithm 4).  A block mask turns
+ * both passes into the block-sparse variant (Section 3.3 / Algorithm 5).
+ *
+ * General conventions
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller.  The
+ *     library never allocates, frees, or keeps a pointer after a call returns.
+ *   - Q, K, V, O, dO, dQ, dK, dV are [B, H, N, d] arrays of 16-bit floats
+ *     (fp16 or bf16, chosen by attn_params.dtype) with d contiguous; the
+ *     element strides of the b, h and n axes are given in attn_params and are
+ *     shared by all of these tensors (all three 0 = densely packed).
+ *   - LSE is a packed [B, H, N] float array: L_i = m_i + ln(l_i), the natural
+ *     logsumexp of row i of the scaled, masked logits.  It replaces the pair
+ *     (l, m) that Algorithm 2 saves; P_ij = exp(S_ij - L_i).
+ *   - Calls are asynchronous on attn_params.stream (a hipStream_t, may be
+ *     NULL for the default stream), never synchronise the device, and may be
+ *     issued concurrently from several host threads.
+ *   - Outputs are fully overwritten; the caller need not clear them.
+ *   - A query row that sees no key (possible only through a block mask) gets
+ *     O = 0, LSE = -inf and contributes zero gradients.
+ *   - All argument checks happen on the host before anything is launched.
+ *     Functions return ATTN_OK (0) or a negative attn_status; they never
+ *     abort, throw, or print.
+ *
+ * Supported in this version: d in {64, 128}; N a positive multiple of 128;
+ * tau finite and > 0; 0 <= p_drop < 1; mask_block == 128.
+ */
+#ifndef ATTN_H_
+#define ATTN_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  ATTN_OK = 0,
+  ATTN_ERR_NULL = -1,       /* a required pointer is NULL */
+  ATTN_ERR_SHAPE = -2,      /* B, H, N out of range, N not a multiple of 128, bad strides */
+  ATTN_ERR_DTYPE = -3,      /* dtype is neither ATTN_FP16 nor ATTN_BF16 */
+  ATTN_ERR_HEADDIM = -4,    /* d not in {64, 128} */
+  ATTN_ERR_DROPOUT_P = -5,  /* p_drop not in [0, 1) or NaN */
+  ATTN_ERR_SCALE = -6,      /* softmax_scale not finite or <= 0 */
+  ATTN_ERR_WORKSPACE = -7,  /* workspace NULL, misaligned (256 B) or too small */
+  ATTN_ERR_MASK = -8,       /* mask_block != 128 or negative mask stride */
+  ATTN_ERR_LAUNCH = -9      /* the HIP runtime refused the launch */
+} attn_status;
+
+enum { ATTN_FP16 = 0, ATTN_BF16 = 1 };
+
+typedef struct {
+  int32_t B, H, N, d;        /* problem sizes */
+  int32_t dtype;             /* ATTN_FP16 or ATTN_BF16 */
+  int64_t stride_b;          /* element strides of the [B,H,N,d] tensors;    */
+  int64_t stride_h;          /*   all three zero means packed                */
+  int64_t stride_n;          /*   (stride_n >= d, d itself has stride 1)     */
+  float softmax_scale;       /* tau: multiplies Q K^T before mask and softmax */
+  int32_t causal;            /* != 0: key j is visible to query i iff j <= i */
+  float dropout_p;           /* p_drop in [0,1); 0 switches the generator off */
+  uint64_t seed;             /* Philox key   (the saved generator state R)   */
+  uint64_t offset;           /* low 32 bits enter the Philox counter         */
+  int32_t o_fp32;            /* != 0: O is read/written as float32 [B,H,N,d] packed
+                                with the same strides, instead of dtype      */
+  void* stream;              /* hipStream_t, borrowed for the call           */
+} attn_params;
+
+/*
+ * Dropout mask (bit-exact contract, shared with nothing but this text):
+ * Philox-4x32 with 10 rounds (Salmon et al., SC'11), key = (seed low word,
+ * seed high word), counter = (j / 4, i, b * H + h, offset low word) for query
+ * row i and key column j of head (b, h); element (i, j) takes output word
+ * j % 4 and is KEPT iff word >= floor((double)dropout_p * 2^32).  Kept
+ * probabilities are multiplied by 1 / (1 - dropout_p).  The mask depends on
+ * indices only, so the backward pass regenerates it (Appendix B.4, obs. 1).
+ */
+
+/*
+ * Forward pass (Algorithm 2; Algorithm 1 when causal = 0 and dropout_p = 0).
+ *   Q, K, V : in,  [B,H,N,d] dtype
+ *   O       : out, [B,H,N,d] dtype (or float32 when o_fp32)
+ *   LSE     : out, [B,H,N] float32, packed
+ */
+int attn_fwd(const attn_params* p, const void* Q, const void* K, const void* V,
+             void* O, float* LSE);
+
+/*
+ * Bytes of scratch that attn_bwd / attn_blocksparse_bwd need for these
+ * params: linear in B*H*N*d, never quadratic in N.  Returns 0 if the params
+ * are invalid.
+ */
+size_t attn_bwd_workspace_bytes(const attn_params* p);
+
+/*
+ * Backward pass (Algorithm 4, with D_i = rowsum(dO_i o O_i) from Eq. (4) of
+ * Appendix B.2).
+ *   Q, K, V, O, dO : in,  [B,H,N,d] (O as written by attn_fwd with the same params)
+ *   LSE            : in,  [B,H,N] float32 from attn_fwd
+ *   dQ, dK, dV     : out, [B,H,N,d] dtype
+ *   workspace      : device scratch, 256-byte aligned, >= attn_bwd_workspace_bytes(p);
+ *                    contents on entry are ignored and on exit unspecified
+ */
+int attn_bwd(const attn_params* p, const void* Q, const void* K, const void* V,
+             const void* O, const void* dO, const float* LSE,
+             void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes);
+
+/*
+ * Block-sparse forward (Section 3.3, Algorithm 5): as attn_fwd, but entry
+ * (i, j) is additionally masked out unless
+ * block_mask[(i / mask_block) * T + (j / mask_block)] != 0, T = N / mask_block;
+ * tiles whose block is zero are skipped, not computed.
+ *   block_mask    : in, device uint8 [T, T] row-major (per head if mask_stride_h != 0)
+ *   mask_block    : must be 128
+ *   mask_stride_h : bytes between the masks of consecutive heads h (0 = one
+ *                   mask shared by all heads; batches always share)
+ */
+int attn_blocksparse_fwd(const attn_params* p, const uint8_t* block_mask, int32_t mask_block,
+                         int64_t mask_stride_h, const void* Q, const void* K, const void* V,
+                         void* O, float* LSE);
+
+/*
+ * Block-sparse backward: Algorithm 4 restricted to the non-zero blocks (the
+ * paper states only that the backward skips the same blocks, Section 3.3).
+ * Arguments as attn_bwd plus the mask arguments of attn_blocksparse_fwd.
+ */
+int attn_blocksparse_bwd(const attn_params* p, const uint8_t* block_mask, int32_t mask_block,
+                         int64_t mask_stride_h, const void* Q, const void* K, const void* V,
+                         const void* O, const void* dO, const float* LSE,
+                         void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes);
+
+/*
+ * Test hook: writes the dropout keep mask the kernels use, keep[b][h][i][j] in
+ * {0, 1}, as a packed device uint8 [B,H,N,N] array (N*N bytes per head: only
+ * for small problems).  Uses B, H, N, dropout_p, seed, offset, stream of p.
+ */
+int attn_debug_dropout_mask(const attn_params* p, uint8_t* keep);
+
+/* Static, human-readable text for a status code. */
+const char* attn_strerror(int status);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int attn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ATTN_H_ */

@@ -1,0 +1,177 @@
+// C-ABI front end: argument checks (host only, before any launch) and kernel dispatch.
+#include "../../include/attn.h"
+#include "attn_common.h"
+
+#include <cmath>
+#include <cstring>
+
+namespace {
+
+constexpr int kVersion = 100;  // 0.1.0
+
+struct Checked {
+  attn::KArgs k;
+  int dtype, d;
+  bool causal, dropout;
+  hipStream_t stream;
+};
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Validates everything that does not involve tensor pointers and fills the kernel arguments.
+int check_params(const attn_params* p, Checked* out) {
+  if (p == nullptr) return ATTN_ERR_NULL;
+  if (p->dtype != ATTN_FP16 && p->dtype != ATTN_BF16) return ATTN_ERR_DTYPE;
+  if (p->d != 64 && p->d != 128) return ATTN_ERR_HEADDIM;
+  if (p->B <= 0 || p->H <= 0 || p->N <= 0) return ATTN_ERR_SHAPE;
+  if (p->N % attn::kMaskBlock != 0) return ATTN_ERR_SHAPE;
+  if ((int64_t)p->B * p->H > (int64_t)1 << 24) return ATTN_ERR_SHAPE;
+  if ((int64_t)p->B * p->H * (p->N / attn::kMaskBlock) > (int64_t)1 << 28) return ATTN_ERR_SHAPE;
+  int64_t sb = p->stride_b, sh = p->stride_h, sn = p->stride_n;
+  if (sb == 0 && sh == 0 && sn == 0) {
+    sn = p->d;
+    sh = (int64_t)p->N * p->d;
+    sb = (int64_t)p->H * sh;
+  }
+  // rows must start on 16-byte boundaries for the vector loads
+  if (sn < p->d || sn % 8 != 0 || sh % 8 != 0 || sb % 8 != 0 || sh < 0 || sb < 0) return ATTN_ERR_SHAPE;
+  if (!(p->dropout_p >= 0.0f && p->dropout_p < 1.0f)) return ATTN_ERR_DROPOUT_P;
+  if (!std::isfinite(p->softmax_scale) || !(p->softmax_scale > 0.0f)) return ATTN_ERR_SCALE;
+
+  attn::KArgs& k = out->k;
+  std::memset(&k, 0, sizeof(k));
+  k.sb = sb; k.sh = sh; k.sn = sn;
+  k.B = p->B; k.H = p->H; k.N = p->N; k.T = p->N / attn::kMaskBlock;
+  k.tau = p->softmax_scale;
+  k.scale_log2 = (float)((double)p->softmax_scale * 1.4426950408889634);
+  k.keep_scale = 1.0f / (1.0f - p->dropout_p);
+  k.drop_thr = (uint32_t)std::floor((double)p->dropout_p * 4294967296.0);
+  k.seed_lo = (uint32_t)(p->seed & 0xFFFFFFFFu);
+  k.seed_hi = (uint32_t)(p->seed >> 32);
+  k.offset_lo = (uint32_t)(p->offset & 0xFFFFFFFFu);
+  k.o_fp32 = p->o_fp32 != 0;
+  out->dtype = p->dtype;
+  out->d = p->d;
+  out->causal = p->causal != 0;
+  out->dropout = p->dropout_p > 0.0f;
+  out->stream = (hipStream_t)p->stream;
+  return ATTN_OK;
+}
+
+int check_mask(const uint8_t* block_mask, int32_t mask_block, int64_t mask_stride_h, const attn_params* p) {
+  if (block_mask == nullptr) return ATTN_ERR_NULL;
+  if (mask_block != attn::kMaskBlock) return ATTN_ERR_MASK;
+  const int64_t T = p->N / attn::kMaskBlock;
+  if (mask_stride_h < 0 || (mask_stride_h != 0 && mask_stride_h < T * T)) return ATTN_ERR_MASK;
+  return ATTN_OK;
+}
+
+void set_items(attn::KArgs& k, int tiles_per_head) {
+  k.n_items = k.B * k.H * tiles_per_head;
+  k.chunk = (k.n_items + attn::kXcds - 1) / attn::kXcds;
+}
+
+int fwd_common(const attn_params* p, const uint8_t* mask, int64_t mask_sh, bool sparse,
+               const void* Q, const void* K, const void* V, void* O, float* LSE) {
+  Checked c;
+  const int st = check_params(p, &c);
+  if (st != ATTN_OK) return st;
+  if (!Q || !K || !V || !O || !LSE) return ATTN_ERR_NULL;
+  c.k.Q = Q; c.k.K = K; c.k.V = V; c.k.O = O; c.k.LSE = LSE;
+  c.k.mask = mask; c.k.mask_sh = mask_sh;
+  set_items(c.k, c.k.N / 128);
+  const int e = attn::launch_fwd(c.k, c.dtype, c.d, c.causal, c.dropout, sparse, c.stream);
+  return e == 0 ? ATTN_OK : ATTN_ERR_LAUNCH;
+}
+
+int bwd_common(const attn_params* p, const uint8_t* mask, int64_t mask_sh, bool sparse,
+               const void* Q, const void* K, const void* V, const void* O, const void* dO,
+               const float* LSE, void* dQ, void* dK, void* dV, void* ws, size_t ws_bytes) {
+  Checked c;
+  const int st = check_params(p, &c);
+  if (st != ATTN_OK) return st;
+  if (!Q || !K || !V || !O || !dO || !LSE || !dQ || !dK || !dV) return ATTN_ERR_NULL;
+  const size_t need = attn_bwd_workspace_bytes(p);
+  if (ws == nullptr || ((uintptr_t)ws & 255u) != 0 || ws_bytes < need) return ATTN_ERR_WORKSPACE;
+  c.k.Q = Q; c.k.K = K; c.k.V = V; c.k.O = const_cast<void*>(O); c.k.LSE = const_cast<float*>(LSE);
+  c.k.dO = dO; c.k.dQ = dQ; c.k.dK = dK; c.k.dV = dV;
+  c.k.Dvec = (float*)ws;
+  c.k.mask = mask; c.k.mask_sh = mask_sh;
+  set_items(c.k, c.k.N / 128);
+  const int e = attn::launch_bwd(c.k, c.dtype, c.d, c.causal, c.dropout, sparse, c.stream);
+  return e == 0 ? ATTN_OK : ATTN_ERR_LAUNCH;
+}
+
+}  // namespace
+
+extern "C" {
+
+int attn_fwd(const attn_params* p, const void* Q, const void* K, const void* V, void* O, float* LSE) {
+  return fwd_common(p, nullptr, 0, false, Q, K, V, O, LSE);
+}
+
+size_t attn_bwd_workspace_bytes(const attn_params* p) {
+  Checked c;
+  if (check_params(p, &c) != ATTN_OK) return 0;
+  // D_i = rowsum(dO_i o O_i): one float per row
+  return align_up((size_t)p->B * p->H * p->N * sizeof(float), 256);
+}
+
+int attn_bwd(const attn_params* p, const void* Q, const void* K, const void* V, const void* O,
+             const void* dO, const float* LSE, void* dQ, void* dK, void* dV, void* workspace,
+             size_t workspace_bytes) {
+  return bwd_common(p, nullptr, 0, false, Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes);
+}
+
+int attn_blocksparse_fwd(const attn_params* p, const uint8_t* block_mask, int32_t mask_block,
+                         int64_t mask_stride_h, const void* Q, const void* K, const void* V, void* O,
+                         float* LSE) {
+  Checked c;
+  int st = check_params(p, &c);
+  if (st != ATTN_OK) return st;
+  st = check_mask(block_mask, mask_block, mask_stride_h, p);
+  if (st != ATTN_OK) return st;
+  return fwd_common(p, block_mask, mask_stride_h, true, Q, K, V, O, LSE);
+}
+
+int attn_blocksparse_bwd(const attn_params* p, const uint8_t* block_mask, int32_t mask_block,
+                         int64_t mask_stride_h, const void* Q, const void* K, const void* V,
+                         const void* O, const void* dO, const float* LSE, void* dQ, void* dK, void* dV,
+                         void* workspace, size_t workspace_bytes) {
+  Checked c;
+  int st = check_params(p, &c);
+  if (st != ATTN_OK) return st;
+  st = check_mask(block_mask, mask_block, mask_stride_h, p);
+  if (st != ATTN_OK) return st;
+  return bwd_common(p, block_mask, mask_stride_h, true, Q, K, V, O, dO, LSE, dQ, dK, dV, workspace,
+                    workspace_bytes);
+}
+
+int attn_debug_dropout_mask(const attn_params* p, uint8_t* keep) {
+  Checked c;
+  const int st = check_params(p, &c);
+  if (st != ATTN_OK) return st;
+  if (keep == nullptr) return ATTN_ERR_NULL;
+  const int e = attn::launch_dropout_mask(c.k, keep, c.stream);
+  return e == 0 ? ATTN_OK : ATTN_ERR_LAUNCH;
+}
+
+const char* attn_strerror(int status) {
+  switch (status) {
+    case ATTN_OK: return "ok";
+    case ATTN_ERR_NULL: return "a required pointer is NULL";
+    case ATTN_ERR_SHAPE: return "unsupported shape or strides (N must be a positive multiple of 128)";
+    case ATTN_ERR_DTYPE: return "dtype must be ATTN_FP16 or ATTN_BF16";
+    case ATTN_ERR_HEADDIM: return "head dimension must be 64 or 128";
+    case ATTN_ERR_DROPOUT_P: return "dropout_p must be in [0, 1)";
+    case ATTN_ERR_SCALE: return "softmax_scale must be finite and positive";
+    case ATTN_ERR_WORKSPACE: return "workspace is NULL, not 256-byte aligned, or too small";
+    case ATTN_ERR_MASK: return "mask_block must be 128 and mask_stride_h 0 or >= T*T";
+    case ATTN_ERR_LAUNCH: return "kernel launch failed";
+    default: return "unknown status";
+  }
+}
+
+int attn_version(void) { return kVersion; }
+
+}  // extern "C"

@@ -1,0 +1,94 @@
+// Internal declarations shared by the gfx950 attention kernels and the C-ABI front end.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace attn {
+
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// Problem description handed to every kernel (plain data, passed by value).
+struct KArgs {
+  const void* Q; const void* K; const void* V;
+  void* O;                 // fwd: out; bwd: in
+  float* LSE;              // fwd: out; bwd: in        [B,H,N]
+  const void* dO;          // bwd in
+  void* dQ; void* dK; void* dV;   // bwd out
+  float* Dvec;             // bwd scratch: D_i = rowsum(dO_i o O_i)   [B,H,N]
+  const uint8_t* mask;     // block mask [T,T] (per head if mask_sh != 0) or nullptr
+  int64_t mask_sh;
+  int64_t sb, sh, sn;      // element strides of the [B,H,N,d] tensors
+  int B, H, N, T;          // T = N / 128
+  float tau;               // softmax scale
+  float scale_log2;        // tau * log2(e)
+  float keep_scale;        // 1 / (1 - p_drop)
+  uint32_t drop_thr;       // keep iff philox word >= drop_thr
+  uint32_t seed_lo, seed_hi, offset_lo;
+  int o_fp32;
+  int n_items;             // work items (B*H*tiles)
+  int chunk;               // items per XCD = ceil(n_items / 8)
+};
+
+enum { kXcds = 8, kMaskBlock = 128 };
+
+// Launchers (defined in the .hip files).  dtype: 0 fp16, 1 bf16.  Return hipError_t as int.
+int launch_fwd(const KArgs& a, int dtype, int d, bool causal, bool dropout, bool sparse, hipStream_t s);
+int launch_bwd(const KArgs& a, int dtype, int d, bool causal, bool dropout, bool sparse, hipStream_t s);
+int launch_dropout_mask(const KArgs& a, uint8_t* keep, hipStream_t s);
+
+#if defined(__HIPCC__)
+// ---------------------------------------------------------------- device helpers
+template <typename T> struct Vec;
+template <> struct Vec<_Float16> { typedef f16x8 x8; typedef f16x4 x4; };
+template <> struct Vec<__bf16> { typedef bf16x8 x8; typedef bf16x4 x4; };
+
+__device__ __forceinline__ f32x16 mfma32(f16x8 a, f16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// Philox-4x32-10 (Salmon et al., SC'11): counter (c0..c3), key (k0,k1) -> 4 words.
+__device__ __forceinline__ u32x4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                               uint32_t k0, uint32_t k1) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+    const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+    const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+    const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+    c1 = (uint32_t)p1; c3 = (uint32_t)p0; c0 = n0; c2 = n2;
+    k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+  }
+  u32x4 r = {c0, c1, c2, c3};
+  return r;
+}
+
+// value of the lane 32 positions away (wave64)
+__device__ __forceinline__ float xchg32(float x) {
+  const uint32_t u = __builtin_bit_cast(uint32_t, x);
+  auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  // r[0] = {lo half, lo half}, r[1] = {hi half, hi half}
+  const uint32_t other = (threadIdx.x & 32) ? r[0] : r[1];
+  return __builtin_bit_cast(float, other);
+}
+
+// Work-item index for this workgroup: consecutive items share an XCD (workgroups are
+// dealt round-robin to the 8 XCDs, each with its own L2).  Returns -1 for padding groups.
+__device__ __forceinline__ int xcd_item(int n_items, int chunk) {
+  const int id = blockIdx.x;
+  const int item = (id % kXcds) * chunk + id / kXcds;
+  return item < n_items && (id / kXcds) < chunk ? item : -1;
+}
+#endif  // __HIPCC__
+
+}  // namespace attn

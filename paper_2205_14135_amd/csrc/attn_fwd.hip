@@ -1,0 +1,332 @@
+// Forward pass of IO-aware exact attention for gfx950 (MI355X).
+//
+// What is computed is Algorithm 2 of the paper (Appendix B.3): S = tau Q K^T, mask, online
+// softmax with running row max m and row sum l, dropout on the unnormalised probabilities,
+// O accumulation with rescaling, and the saved statistic L = m + ln l.  The loop order is
+// NOT the paper's: a workgroup owns a 128-row Q tile (4 wavefronts x 32 rows), keeps O, m, l
+// in registers for the whole sweep over K/V tiles and writes O and L exactly once, so O, m, l
+// never travel to HBM between tiles (the paper's K/V-outer order re-reads and re-writes them
+// on every pass).  K/V tiles of 64 keys are staged in LDS.
+//
+// Register layout trick: the kernel computes S^T = K Q^T with 32x32x16 MFMA, so that a lane
+// holds 16 keys of ONE query (accumulator register i of key block kb is key
+// 32 kb + 8 (i/4) + 4 (lane/32) + i%4, query lane%32).  Row max / row sum are then in-lane
+// reductions plus one exchange with lane^32, the rescale factor is a per-lane scalar, and the
+// probabilities are already in the B-operand layout of the second product O^T = V^T P^T.
+// V^T fragments come from the row-major V tile in LDS through the gfx950 transposing LDS read.
+#include "attn_common.h"
+
+namespace attn {
+namespace {
+
+constexpr int BR = 128;  // query rows per workgroup
+constexpr int BC = 64;   // keys per K/V tile
+constexpr int NT = 256;  // threads
+
+template <int D> struct Lds {
+  static constexpr int KS = D + 8;    // K row stride (elements): 16-byte row skew, conflict-free b128 reads
+  static constexpr int VS = D + 32;   // V row stride: consecutive rows 16 banks apart for the transposing read
+  static constexpr int K_ELEMS = BC * KS;
+  static constexpr int V_ELEMS = BC * VS;
+};
+
+// Iterates over the 64-key tiles this Q tile must visit, in increasing order.
+// Dense: 0 .. n-1.  Sparse: the two 64-key halves of every non-zero 128x128 block of mask row qt.
+// All state is wavefront-uniform.
+template <bool SPARSE> struct TileIter {
+  const uint8_t* row;  // mask row (sparse)
+  int limit;           // number of 128-blocks (sparse) or 64-tiles (dense) to consider
+  int pos;             // dense: next tile; sparse: next 64-block chunk base
+  uint64_t bits;       // sparse: pending blocks of the current chunk
+  int base;            // sparse: block index of bit 0
+  int half;            // sparse: pending second half (tile index) or -1
+  __device__ void init(const uint8_t* mask_row, int lim) {
+    row = mask_row; limit = lim; pos = 0; bits = 0; base = 0; half = -1;
+  }
+  __device__ int next() {
+    if constexpr (!SPARSE) {
+      return pos < limit ? pos++ : -1;
+    } else {
+      if (half >= 0) { const int t = half; half = -1; return t; }
+      while (bits == 0) {
+        if (pos >= limit) return -1;
+        const int lane = threadIdx.x & 63;
+        const int blk = pos + lane;
+        const bool on = blk < limit && row[blk] != 0;
+        bits = __ballot(on);
+        base = pos;
+        pos += 64;
+      }
+      const int b = __builtin_ctzll(bits);
+      bits &= bits - 1;
+      const int blk = base + b;
+      half = 2 * blk + 1;
+      return 2 * blk;
+    }
+  }
+};
+
+template <typename T, int D, bool CAUSAL, bool DROPOUT, bool SPARSE>
+__global__ __launch_bounds__(NT, 2) void fwd_kernel(const KArgs a) {
+  typedef typename Vec<T>::x8 T8;
+  typedef typename Vec<T>::x4 T4;
+  typedef Lds<D> L;
+  constexpr int KK = D / 16;        // MFMA k-steps over the head dimension
+  constexpr int DB = D / 32;        // 32-row blocks of O^T
+  constexpr int CPR = D / 8;        // 16-byte chunks per row
+  constexpr int RPP = NT / CPR;     // rows per load pass
+  constexpr int NP = BC / RPP;      // load passes per tile
+
+  __shared__ __attribute__((aligned(16))) T Ks[L::K_ELEMS];
+  __shared__ __attribute__((aligned(16))) T Vs[L::V_ELEMS];
+
+  const int item = xcd_item(a.n_items, a.chunk);
+  if (item < 0) return;
+  const int n_qt = a.N / BR;
+  const int bh = item / n_qt;
+  // heavy (late) tiles first under a causal mask
+  const int qt = CAUSAL ? (n_qt - 1 - item % n_qt) : item % n_qt;
+  const int b = bh / a.H, h = bh % a.H;
+  const int64_t head_off = (int64_t)b * a.sb + (int64_t)h * a.sh;
+  const T* __restrict__ Qg = (const T*)a.Q + head_off;
+  const T* __restrict__ Kg = (const T*)a.K + head_off;
+  const T* __restrict__ Vg = (const T*)a.V + head_off;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int r = lane & 31, g = lane >> 5;
+  const int q0 = qt * BR + wave * 32;  // first query row of this wavefront
+  const int qi = q0 + r;               // this lane's query row
+
+  // Q^T fragments (B operand): lane holds query qi, d = 16 kk + 8 g .. +7
+  T8 qf[KK];
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk)
+    qf[kk] = *(const T8*)(Qg + (int64_t)qi * a.sn + 16 * kk + 8 * g);
+
+  f32x16 o[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
+  float m_run = -INFINITY;  // running max of the scaled logits, base-2 domain
+  float l_run = 0.f;        // this lane's share of the running row sum
+
+  TileIter<SPARSE> it;
+  {
+    int lim;
+    if constexpr (SPARSE) lim = CAUSAL ? qt + 1 : a.T;
+    else lim = CAUSAL ? 2 * qt + 2 : a.N / BC;
+    it.init(SPARSE ? a.mask + (int64_t)h * a.mask_sh + (int64_t)qt * a.T : nullptr, lim);
+  }
+
+  // global -> register staging of one K/V tile
+  const int lrow = tid / CPR, lchunk = tid % CPR;
+  T8 kreg[NP], vreg[NP];
+  auto gload = [&](int jt) {
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+      const int64_t off = (int64_t)(jt * BC + p * RPP + lrow) * a.sn + 8 * lchunk;
+      kreg[p] = *(const T8*)(Kg + off);
+      vreg[p] = *(const T8*)(Vg + off);
+    }
+  };
+  auto sstore = [&]() {
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+      *(T8*)(Ks + (p * RPP + lrow) * L::KS + 8 * lchunk) = kreg[p];
+      *(T8*)(Vs + (p * RPP + lrow) * L::VS + 8 * lchunk) = vreg[p];
+    }
+  };
+
+  // transposing-read address pattern: 16-lane group q16 covers d columns 16 (q16 & 1) .. +15 of
+  // a 32-row d block, lanes 4t+j of the group point at key row t, columns 4j .. 4j+3
+  const int i16 = lane & 15, q16 = lane >> 4;
+  const int v_lane_off = (4 * g + (i16 >> 2)) * L::VS + 16 * (q16 & 1) + 4 * (i16 & 3);
+
+  const float c = a.scale_log2;
+  int jt = it.next();
+  if (jt >= 0) gload(jt);
+  while (jt >= 0) {
+    sstore();
+    __syncthreads();
+    const int jn = it.next();
+    if (jn >= 0) gload(jn);
+
+    const int k0 = jt * BC;
+    const bool wave_active = !CAUSAL || k0 <= q0 + 31;
+    if (wave_active) {
+      // ---- S^T = K Q^T  (64 keys x 32 queries per wavefront)
+      f32x16 s[2];
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s[kb][i] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+          const T8 kf = *(const T8*)(Ks + (32 * kb + r) * L::KS + 16 * kk + 8 * g);
+          s[kb] = mfma32(kf, qf[kk], s[kb]);
+        }
+      }
+      // ---- causal mask on tiles that cross the diagonal
+      if (CAUSAL && k0 + BC - 1 > q0) {
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const int key = k0 + 32 * kb + 8 * (i >> 2) + 4 * g + (i & 3);
+            if (key > qi) s[kb][i] = -INFINITY;
+          }
+      }
+      // ---- online softmax (base 2): row max, rescale factor, probabilities, row sum
+      float mx = s[0][0];
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[kb][i]);
+      mx = fmaxf(mx, xchg32(mx));
+      const float m_new = fmaxf(m_run, mx * c);
+      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
+      m_run = m_new;
+      float psum = 0.f;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][i], c, -m_use));
+          s[kb][i] = p;
+          psum += p;
+        }
+      l_run = l_run * alpha + psum;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
+      // ---- dropout on the unnormalised probabilities (the row sum above is undropped)
+      if constexpr (DROPOUT) {
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int i4 = 0; i4 < 4; ++i4) {
+            const uint32_t jg = (uint32_t)(k0 + 32 * kb + 8 * i4 + 4 * g) >> 2;
+            const u32x4 w = philox4x32_10(jg, (uint32_t)qi, (uint32_t)bh, a.offset_lo, a.seed_lo, a.seed_hi);
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (w[e] < a.drop_thr) s[kb][4 * i4 + e] = 0.f;
+          }
+      }
+      // ---- P^T fragments (B operand): 16-key chunk cc = 2 kb + half
+      T8 pf[4];
+#pragma unroll
+      for (int cc = 0; cc < 4; ++cc)
+#pragma unroll
+        for (int t = 0; t < 8; ++t) pf[cc][t] = (T)s[cc >> 1][8 * (cc & 1) + t];
+      // ---- O^T += V^T P^T
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc) {
+          const T* vp = Vs + v_lane_off + (16 * cc) * L::VS + 32 * db;
+          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (__attribute__((address_space(3))) s16x4*)(vp));
+          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (__attribute__((address_space(3))) s16x4*)(vp + 8 * L::VS));
+          const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+          o[db] = mfma32(__builtin_bit_cast(T8, both), pf[cc], o[db]);
+        }
+      }
+    }
+    __syncthreads();
+    jt = jn;
+  }
+
+  // ---- epilogue: normalise, apply the dropout scale, write O and L once
+  const float l_tot = l_run + xchg32(l_run);
+  const float inv = l_tot > 0.f ? (DROPOUT ? a.keep_scale : 1.f) / l_tot : 0.f;
+  if (g == 0) {
+    const float lse = l_tot > 0.f ? (m_run + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f : -INFINITY;
+    a.LSE[(int64_t)bh * a.N + qi] = lse;
+  }
+  if (a.o_fp32) {
+    float* Og = (float*)a.O + head_off + (int64_t)qi * a.sn;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        f32x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = o[db][4 * i4 + e] * inv;
+        *(f32x4*)(Og + 32 * db + 8 * i4 + 4 * g) = v;
+      }
+  } else {
+    T* Og = (T*)a.O + head_off + (int64_t)qi * a.sn;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        T4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = (T)(o[db][4 * i4 + e] * inv);
+        *(T4*)(Og + 32 * db + 8 * i4 + 4 * g) = v;
+      }
+  }
+}
+
+template <typename T, int D>
+int launch_fwd_td(const KArgs& a, bool causal, bool dropout, bool sparse, hipStream_t s) {
+  const dim3 grid(kXcds * a.chunk), block(NT);
+#define ATTN_FWD_CASE(C, P, S)                                                         \
+  if (causal == C && dropout == P && sparse == S) {                                    \
+    hipLaunchKernelGGL((fwd_kernel<T, D, C, P, S>), grid, block, 0, s, a);             \
+    return (int)hipGetLastError();                                                     \
+  }
+  ATTN_FWD_CASE(false, false, false)
+  ATTN_FWD_CASE(true, false, false)
+  ATTN_FWD_CASE(false, true, false)
+  ATTN_FWD_CASE(true, true, false)
+  ATTN_FWD_CASE(false, false, true)
+  ATTN_FWD_CASE(true, false, true)
+  ATTN_FWD_CASE(false, true, true)
+  ATTN_FWD_CASE(true, true, true)
+#undef ATTN_FWD_CASE
+  return (int)hipErrorInvalidValue;
+}
+
+// keep[bh][i][j] for the test hook: one thread per group of four consecutive keys
+__global__ void dropout_mask_kernel(const KArgs a, uint8_t* keep) {
+  const int64_t ngrp = (int64_t)a.N / 4;
+  const int64_t total = (int64_t)a.B * a.H * a.N * ngrp;
+  for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
+       idx += (int64_t)gridDim.x * blockDim.x) {
+    const uint32_t jg = (uint32_t)(idx % ngrp);
+    const uint32_t i = (uint32_t)((idx / ngrp) % a.N);
+    const uint32_t bh = (uint32_t)(idx / (ngrp * a.N));
+    const u32x4 w = philox4x32_10(jg, i, bh, a.offset_lo, a.seed_lo, a.seed_hi);
+    uint32_t packed = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) packed |= (w[e] >= a.drop_thr ? 1u : 0u) << (8 * e);
+    *(uint32_t*)(keep + idx * 4) = packed;
+  }
+}
+
+}  // namespace
+
+int launch_fwd(const KArgs& a, int dtype, int d, bool causal, bool dropout, bool sparse, hipStream_t s) {
+  if (dtype == 0 && d == 64) return launch_fwd_td<_Float16, 64>(a, causal, dropout, sparse, s);
+  if (dtype == 0 && d == 128) return launch_fwd_td<_Float16, 128>(a, causal, dropout, sparse, s);
+  if (dtype == 1 && d == 64) return launch_fwd_td<__bf16, 64>(a, causal, dropout, sparse, s);
+  if (dtype == 1 && d == 128) return launch_fwd_td<__bf16, 128>(a, causal, dropout, sparse, s);
+  return (int)hipErrorInvalidValue;
+}
+
+int launch_dropout_mask(const KArgs& a, uint8_t* keep, hipStream_t s) {
+  const int64_t total = (int64_t)a.B * a.H * a.N * (a.N / 4);
+  const int blocks = (int)((total + 255) / 256 < 65536 ? (total + 255) / 256 : 65536);
+  hipLaunchKernelGGL(dropout_mask_kernel, dim3(blocks), dim3(256), 0, s, a, keep);
+  return (int)hipGetLastError();
+}
+
+}  // namespace attn

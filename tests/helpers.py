@@ -1,0 +1,84 @@
+"""Shared plumbing for the GPU parity tests: seeded inputs -> (HIP library, fp64 oracle)."""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+import torch
+
+from oracle import attention_oracle as orc
+from paper_2205_14135_amd import binding, inputs
+
+FWD_ATOL = 1e-2       # forward max-abs bar (fp16/bf16 inputs, fp32 accumulation)
+GRAD_REL_L2 = 2e-2    # dQ/dK/dV relative-L2 bar
+LSE_ATOL = 2e-3
+
+
+def ulp_half(x: np.ndarray, dtype: str) -> np.ndarray:
+    """Half a unit in the last place of the 16-bit output type at magnitude |x|."""
+    mant = {"bf16": 8, "fp16": 11}[dtype]
+    e = np.floor(np.log2(np.maximum(np.abs(x), 2.0 ** -14)))
+    return 2.0 ** (e - mant)
+
+
+def make_case(B, H, N, d, dtype, seed):
+    t = inputs.gaussian_tensors(B, H, N, d, dtype, seed)
+    dev = {k: inputs.to_torch(v, dtype, "cuda") for k, v in t.items()}
+    return t, dev
+
+
+def rel_l2(a: np.ndarray, b: np.ndarray) -> float:
+    den = float(np.sqrt((b.astype(np.float64) ** 2).sum()))
+    return float(np.sqrt(((a.astype(np.float64) - b) ** 2).sum())) / max(den, 1e-30)
+
+
+def to_np(t: torch.Tensor) -> np.ndarray:
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+def check_forward(t, dev, dtype, tau, *, causal=False, p=0.0, seed=0, offset=0, block_mask=None,
+                  heads=None, rows=None):
+    """Runs fwd through the C ABI twice (dtype O and fp32 O) and compares with the oracle.
+
+    heads: (b, h) pairs the oracle checks (default all); rows: query rows checked (default all).
+    Returns a dict of error figures.
+    """
+    B, H, N, d = t["Q"].shape
+    kw = dict(softmax_scale=tau, causal=causal, dropout_p=p, seed=seed, offset=offset)
+    if block_mask is None:
+        O, L = binding.attn_fwd(dev["Q"], dev["K"], dev["V"], **kw)
+        O32, L32 = binding.attn_fwd(dev["Q"], dev["K"], dev["V"], o_fp32=True, **kw)
+    else:
+        bm = torch.from_numpy(block_mask).cuda()
+        O, L = binding.attn_blocksparse_fwd(dev["Q"], dev["K"], dev["V"], bm, **kw)
+        O32, L32 = binding.attn_blocksparse_fwd(dev["Q"], dev["K"], dev["V"], bm, o_fp32=True, **kw)
+    torch.cuda.synchronize()
+    assert torch.equal(L, L32)
+    O, O32, L = to_np(O), to_np(O32), to_np(L)
+    heads = heads or [(b, h) for b in range(B) for h in range(H)]
+    res = dict(o32=0.0, o=0.0, o_excess=0.0, lse=0.0)
+    for b, h in heads:
+        rr = np.arange(N) if rows is None else np.asarray(rows)
+        keep = orc.dropout_keep_mask(b, h, H, N, p, seed, offset, rows=rr) if p > 0 else None
+        bm_h = None if block_mask is None else (block_mask if block_mask.ndim == 2 else block_mask[h])
+        Oo, Lo = orc.forward_head(t["Q"][b, h], t["K"][b, h], t["V"][b, h], tau, causal=causal,
+                                  p_drop=p, keep=keep, block_mask=bm_h, rows=rr)
+        res["o32"] = max(res["o32"], float(np.abs(O32[b, h][rr] - Oo).max()))
+        err = np.abs(O[b, h][rr] - Oo)
+        res["o"] = max(res["o"], float(err.max()))
+        res["o_excess"] = max(res["o_excess"], float((err - ulp_half(Oo, dtype)).max()))
+        fin = np.isfinite(Lo)
+        assert (np.isfinite(L[b, h][rr]) == fin).all()
+        if fin.any():
+            res["lse"] = max(res["lse"], float(np.abs(L[b, h][rr][fin] - Lo[fin]).max()))
+        if (~fin).any():
+            assert (O[b, h][rr][~fin] == 0).all()
+    return res
+
+
+def assert_forward_ok(res):
+    # computed value (before the 16-bit output rounding) meets the bar outright
+    assert res["o32"] <= FWD_ATOL, res
+    # the 16-bit O meets it up to half a unit in the last place of the output type
+    assert res["o_excess"] <= FWD_ATOL, res
+    assert res["lse"] <= LSE_ATOL, res
