@@ -1,5 +1,424 @@
-// placeholder until the backward kernels land
+// Backward pass of IO-aware exact attention for gfx950 (MI355X).
+//
+// The arithmetic is Algorithm 4 of the paper (Appendix B.4): S and P are recomputed tile by
+// tile from Q, K, V and the saved row statistic, the dropout mask is regenerated from the
+// counter-based generator, D_i = rowsum(dO_i o O_i) replaces the row reduction over P o dP
+// (Eq. (4), Appendix B.2), and
+//     dV = P_dropped^T dO,  dP = (dO V^T) o Z,  dS = P o (dP - D),  dQ = tau dS K,  dK = tau dS^T Q.
+// The schedule differs from the paper's single K/V-outer loop with dQ read-modify-written in
+// HBM: three launches, none of which writes a partial result to HBM.
+//   1. rowdot_kernel : D = rowsum(dO o O)                               (HBM-bound, tiny)
+//   2. dq_kernel     : a workgroup owns 128 query rows and sweeps K/V tiles; dQ stays in
+//                      registers (S^T, dP^T layout: lane = query, like the forward kernel)
+//   3. dkv_kernel    : a workgroup owns 128 keys and sweeps Q/dO tiles; dK, dV stay in registers
+//                      (S, dP layout: lane = key)
+// S and dP are therefore recomputed in both 2 and 3 (seven tile products per (i, j) instead of
+// five) in exchange for no atomics, no fp32 dQ round trip and bit-reproducible gradients.
 #include "attn_common.h"
+
 namespace attn {
-int launch_bwd(const KArgs&, int, int, bool, bool, bool, hipStream_t) { return (int)hipErrorNotSupported; }
+namespace {
+
+constexpr int NT = 256;
+constexpr int TILE = 64;  // rows of the streamed tile (keys in dq_kernel, queries in dkv_kernel)
+
+// ---------------------------------------------------------------------------------------------
+// D_i = sum_d dO[i][d] * O[i][d]
+template <typename T, int D>
+__global__ __launch_bounds__(256) void rowdot_kernel(const KArgs a) {
+  typedef typename Vec<T>::x8 T8;
+  constexpr int CPR = D / 8;  // lanes per row
+  const int64_t rows = (int64_t)a.B * a.H * a.N;
+  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t row = gid / CPR;
+  const int ch = (int)(gid % CPR);
+  float acc = 0.f;
+  if (row < rows) {
+    const int64_t bh = row / a.N, i = row % a.N;
+    const int64_t off = (bh / a.H) * a.sb + (bh % a.H) * a.sh + i * a.sn + 8 * ch;
+    const T8 g = *(const T8*)((const T*)a.dO + off);
+    if (a.o_fp32) {
+      const f32x4 o0 = *(const f32x4*)((const float*)a.O + off);
+      const f32x4 o1 = *(const f32x4*)((const float*)a.O + off + 4);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) acc += (float)g[e] * o0[e] + (float)g[4 + e] * o1[e];
+    } else {
+      const T8 o = *(const T8*)((const T*)a.O + off);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc += (float)g[e] * (float)o[e];
+    }
+  }
+#pragma unroll
+  for (int s = CPR / 2; s >= 1; s >>= 1) acc += __shfl_xor(acc, s);
+  if (row < rows && ch == 0) a.Dvec[row] = acc;
 }
+
+// Stages a [64][D] tile: global -> registers -> swizzled LDS.
+template <typename T, int D> struct TileStage {
+  typedef typename Vec<T>::x8 T8;
+  static constexpr int CPR = D / 8, RPP = NT / CPR, NP = TILE / RPP;
+  T8 reg[NP];
+  __device__ __forceinline__ void load(const T* g, int64_t sn, int row0) {
+    const int lrow = threadIdx.x / CPR, lchunk = threadIdx.x % CPR;
+#pragma unroll
+    for (int p = 0; p < NP; ++p)
+      reg[p] = *(const T8*)(g + (int64_t)(row0 + p * RPP + lrow) * sn + 8 * lchunk);
+  }
+  __device__ __forceinline__ void store(T* lds) const {
+    const int lrow = threadIdx.x / CPR, lchunk = threadIdx.x % CPR;
+#pragma unroll
+    for (int p = 0; p < NP; ++p) *(T8*)(lds + lds_off<D>(p * RPP + lrow, lchunk)) = reg[p];
+  }
+};
+
+// Per-lane LDS offsets for the transposing read of a swizzled tile (see attn_fwd.hip for the
+// access pattern): off[db][hi] addresses rows 4g + t (+8 if hi) of a 16-row chunk, d block db.
+template <int D> struct TrOffsets {
+  int off[D / 32][2];
+  __device__ __forceinline__ void init() {
+    const int lane = threadIdx.x & 63;
+    const int g = lane >> 5, i16 = lane & 15, q16 = lane >> 4;
+#pragma unroll
+    for (int hi = 0; hi < 2; ++hi) {
+      const int row = 4 * g + (i16 >> 2) + 8 * hi;
+#pragma unroll
+      for (int db = 0; db < D / 32; ++db) {
+        const int chunk = 4 * db + 2 * (q16 & 1) + ((i16 & 3) >> 1);
+        off[db][hi] = lds_off<D>(row, chunk) + 4 * (i16 & 1);
+      }
+    }
+  }
+};
+
+template <typename T8>
+__device__ __forceinline__ T8 tr_frag(const void* lds_lo, const void* lds_hi) {
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(lds_lo));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(lds_hi));
+  const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(T8, both);
+}
+
+// Writes a transposed accumulator (rows = d, column = this lane's token) as a token row.
+template <typename T, int D>
+__device__ __forceinline__ void store_rows(T* dst_row, const f32x16 (&acc)[D / 32], float scale, int g) {
+  typedef typename Vec<T>::x4 T4;
+#pragma unroll
+  for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+    for (int i4 = 0; i4 < 4; ++i4) {
+      T4 v;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = (T)(acc[db][4 * i4 + e] * scale);
+      *(T4*)(dst_row + 32 * db + 8 * i4 + 4 * g) = v;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// dQ: workgroup = 128 query rows (4 wavefronts x 32), sweep over 64-key tiles.
+template <typename T, int D, bool CAUSAL, bool DROPOUT, bool SPARSE>
+__global__ __launch_bounds__(NT, 2) void dq_kernel(const KArgs a) {
+  typedef typename Vec<T>::x8 T8;
+  constexpr int KK = D / 16, DB = D / 32;
+  __shared__ __attribute__((aligned(16))) T Ks[TILE * D];
+  __shared__ __attribute__((aligned(16))) T Vs[TILE * D];
+
+  const int item = xcd_item(a.n_items, a.chunk);
+  if (item < 0) return;
+  const int n_qt = a.N / 128;
+  const int bh = item / n_qt;
+  const int qt = CAUSAL ? (n_qt - 1 - item % n_qt) : item % n_qt;
+  const int b = bh / a.H, h = bh % a.H;
+  const int64_t head_off = (int64_t)b * a.sb + (int64_t)h * a.sh;
+  const T* __restrict__ Kg = (const T*)a.K + head_off;
+  const T* __restrict__ Vg = (const T*)a.V + head_off;
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = lane & 31, g = lane >> 5;
+  const int q0 = qt * 128 + wave * 32;
+  const int qi = q0 + r;
+
+  T8 qf[KK], gf[KK];  // Q^T and dO^T fragments (B operands) of this lane's query
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) {
+    const int64_t off = head_off + (int64_t)qi * a.sn + 16 * kk + 8 * g;
+    qf[kk] = *(const T8*)((const T*)a.Q + off);
+    gf[kk] = *(const T8*)((const T*)a.dO + off);
+  }
+  const float lse = a.LSE[(int64_t)bh * a.N + qi];
+  // base-2 statistic; a row that saw no key has P = 0 everywhere
+  const float l2 = (lse == -INFINITY) ? INFINITY : lse * 1.4426950408889634f;
+  const float dsum = a.Dvec[(int64_t)bh * a.N + qi];
+
+  f32x16 dq[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) dq[db][i] = 0.f;
+
+  TileIter<SPARSE> it;
+  {
+    int lim;
+    if constexpr (SPARSE) lim = CAUSAL ? qt + 1 : a.T;
+    else lim = CAUSAL ? 2 * qt + 2 : a.N / TILE;
+    it.init(SPARSE ? a.mask + (int64_t)h * a.mask_sh + (int64_t)qt * a.T : nullptr, 1, 0, lim);
+  }
+  TrOffsets<D> tro;
+  tro.init();
+  TileStage<T, D> ks, vs;
+
+  const float c = a.scale_log2;
+  int jt = it.next();
+  if (jt >= 0) { ks.load(Kg, a.sn, jt * TILE); vs.load(Vg, a.sn, jt * TILE); }
+  while (jt >= 0) {
+    ks.store(Ks);
+    vs.store(Vs);
+    __syncthreads();
+    const int jn = it.next();
+    if (jn >= 0) { ks.load(Kg, a.sn, jn * TILE); vs.load(Vg, a.sn, jn * TILE); }
+
+    const int k0 = jt * TILE;
+    if (!CAUSAL || k0 <= q0 + 31) {
+      f32x16 s[2], dp[2];
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) { s[kb][i] = 0.f; dp[kb][i] = 0.f; }
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk)
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+          const int off = lds_off<D>(32 * kb + r, 2 * kk + g);
+          s[kb] = mfma32(*(const T8*)(Ks + off), qf[kk], s[kb]);     // S^T  = K Q^T
+          dp[kb] = mfma32(*(const T8*)(Vs + off), gf[kk], dp[kb]);   // dP^T = V dO^T
+        }
+      // P = exp(S - L); dS = P o (dP o Z - D)
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+          u32x4 w = {0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu};
+          if constexpr (DROPOUT) {
+            const uint32_t jg = (uint32_t)(k0 + 32 * kb + 8 * i4 + 4 * g) >> 2;
+            w = philox4x32_10(jg, (uint32_t)qi, (uint32_t)bh, a.offset_lo, a.seed_lo, a.seed_hi);
+          }
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int i = 4 * i4 + e;
+            float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][i], c, -l2));
+            if (CAUSAL && k0 + 32 * kb + 8 * i4 + 4 * g + e > qi) p = 0.f;
+            float dpv = dp[kb][i];
+            if constexpr (DROPOUT) dpv = (w[e] >= a.drop_thr) ? dpv * a.keep_scale : 0.f;
+            s[kb][i] = p * (dpv - dsum);
+          }
+        }
+      T8 dsf[4];
+#pragma unroll
+      for (int cc = 0; cc < 4; ++cc)
+#pragma unroll
+        for (int t = 0; t < 8; ++t) dsf[cc][t] = (T)s[cc >> 1][8 * (cc & 1) + t];
+      // dQ^T += K^T dS^T
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc) {
+          const T* base = Ks + 16 * cc * D;
+          dq[db] = mfma32(tr_frag<T8>(base + tro.off[db][0], base + tro.off[db][1]), dsf[cc], dq[db]);
+        }
+    }
+    __syncthreads();
+    jt = jn;
+  }
+  store_rows<T, D>((T*)a.dQ + head_off + (int64_t)qi * a.sn, dq, a.tau, g);
+}
+
+// ---------------------------------------------------------------------------------------------
+// dK, dV: workgroup = 128 keys (4 wavefronts x 32), sweep over 64-query tiles.
+template <typename T, int D, bool CAUSAL, bool DROPOUT, bool SPARSE>
+__global__ __launch_bounds__(NT, 1) void dkv_kernel(const KArgs a) {
+  typedef typename Vec<T>::x8 T8;
+  constexpr int KK = D / 16, DB = D / 32;
+  __shared__ __attribute__((aligned(16))) T Qs[TILE * D];
+  __shared__ __attribute__((aligned(16))) T Gs[TILE * D];   // dO tile
+  __shared__ __attribute__((aligned(16))) float Ls[TILE];   // base-2 row statistic
+  __shared__ __attribute__((aligned(16))) float Ds[TILE];   // D_i
+
+  const int item = xcd_item(a.n_items, a.chunk);
+  if (item < 0) return;
+  const int n_kt = a.N / 128;
+  const int bh = item / n_kt;
+  const int kt = item % n_kt;  // under a causal mask early key blocks are the heavy ones: first
+  const int b = bh / a.H, h = bh % a.H;
+  const int64_t head_off = (int64_t)b * a.sb + (int64_t)h * a.sh;
+  const T* __restrict__ Qg = (const T*)a.Q + head_off;
+  const T* __restrict__ Gg = (const T*)a.dO + head_off;
+  const float* __restrict__ Lg = a.LSE + (int64_t)bh * a.N;
+  const float* __restrict__ Dg = a.Dvec + (int64_t)bh * a.N;
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = lane & 31, g = lane >> 5;
+  const int kw0 = kt * 128 + wave * 32;
+  const int kj = kw0 + r;  // this lane's key
+
+  T8 kf[KK], vf[KK];  // K^T and V^T fragments (B operands) of this lane's key
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) {
+    const int64_t off = head_off + (int64_t)kj * a.sn + 16 * kk + 8 * g;
+    kf[kk] = *(const T8*)((const T*)a.K + off);
+    vf[kk] = *(const T8*)((const T*)a.V + off);
+  }
+  f32x16 dk[DB], dv[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { dk[db][i] = 0.f; dv[db][i] = 0.f; }
+
+  TileIter<SPARSE> it;
+  if constexpr (SPARSE)
+    it.init(a.mask + (int64_t)h * a.mask_sh + kt, a.T, CAUSAL ? kt : 0, a.T);
+  else
+    it.init(nullptr, 0, CAUSAL ? 2 * kt : 0, a.N / TILE);
+  TrOffsets<D> tro;
+  tro.init();
+  TileStage<T, D> qs, gs;
+  float lreg = 0.f, dreg = 0.f;
+  auto load_stats = [&](int row0) {
+    if (threadIdx.x < TILE) {
+      const float lse = Lg[row0 + threadIdx.x];
+      lreg = (lse == -INFINITY) ? INFINITY : lse * 1.4426950408889634f;
+      dreg = Dg[row0 + threadIdx.x];
+    }
+  };
+
+  const float c = a.scale_log2;
+  int itile = it.next();
+  if (itile >= 0) { qs.load(Qg, a.sn, itile * TILE); gs.load(Gg, a.sn, itile * TILE); load_stats(itile * TILE); }
+  while (itile >= 0) {
+    qs.store(Qs);
+    gs.store(Gs);
+    if (threadIdx.x < TILE) { Ls[threadIdx.x] = lreg; Ds[threadIdx.x] = dreg; }
+    __syncthreads();
+    const int inext = it.next();
+    if (inext >= 0) { qs.load(Qg, a.sn, inext * TILE); gs.load(Gg, a.sn, inext * TILE); load_stats(inext * TILE); }
+
+    const int i0 = itile * TILE;
+    if (!CAUSAL || i0 + TILE - 1 >= kw0) {
+      f32x16 s[2], dp[2];
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) { s[qb][i] = 0.f; dp[qb][i] = 0.f; }
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk)
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+          const int off = lds_off<D>(32 * qb + r, 2 * kk + g);
+          s[qb] = mfma32(*(const T8*)(Qs + off), kf[kk], s[qb]);     // S  = Q K^T
+          dp[qb] = mfma32(*(const T8*)(Gs + off), vf[kk], dp[qb]);   // dP = dO V^T
+        }
+      // dropout keep bits: a lane draws for query (r % 4) of each group of four consecutive
+      // queries and the four lanes of a quad (four consecutive keys) exchange the results
+      uint32_t keep_from[4] = {0, 0, 0, 0};
+      if constexpr (DROPOUT) {
+        uint32_t mine = 0;
+#pragma unroll
+        for (int n = 0; n < 8; ++n) {  // n = 4 qb + i4
+          const uint32_t qrow = (uint32_t)(i0 + 32 * (n >> 2) + 8 * (n & 3) + 4 * g + (r & 3));
+          const u32x4 w = philox4x32_10((uint32_t)kj >> 2, qrow, (uint32_t)bh, a.offset_lo, a.seed_lo, a.seed_hi);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) mine |= (w[e] >= a.drop_thr ? 1u : 0u) << (4 * n + e);
+        }
+        // keep_from[e]: bits drawn by the quad lane that handled query e, shifted so that bit 4n
+        // is this lane's key
+        keep_from[0] = (uint32_t)__builtin_amdgcn_mov_dpp((int)mine, 0x00, 0xF, 0xF, true) >> (r & 3);
+        keep_from[1] = (uint32_t)__builtin_amdgcn_mov_dpp((int)mine, 0x55, 0xF, 0xF, true) >> (r & 3);
+        keep_from[2] = (uint32_t)__builtin_amdgcn_mov_dpp((int)mine, 0xAA, 0xF, 0xF, true) >> (r & 3);
+        keep_from[3] = (uint32_t)__builtin_amdgcn_mov_dpp((int)mine, 0xFF, 0xF, 0xF, true) >> (r & 3);
+      }
+      f32x16 pd[2];  // dropped probabilities (without the 1/(1-p) factor, applied at the end)
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+          const f32x4 l4 = *(const f32x4*)(Ls + 32 * qb + 8 * i4 + 4 * g);
+          const f32x4 d4 = *(const f32x4*)(Ds + 32 * qb + 8 * i4 + 4 * g);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int i = 4 * i4 + e;
+            float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[qb][i], c, -l4[e]));
+            if (CAUSAL && kj > i0 + 32 * qb + 8 * i4 + 4 * g + e) p = 0.f;
+            float dpv = dp[qb][i];
+            float pk = p;
+            if constexpr (DROPOUT) {
+              const bool keep = (keep_from[e] >> (4 * (4 * qb + i4))) & 1u;
+              dpv = keep ? dpv * a.keep_scale : 0.f;
+              pk = keep ? p : 0.f;
+            }
+            pd[qb][i] = pk;
+            s[qb][i] = p * (dpv - d4[e]);
+          }
+        }
+      T8 pf[4], dsf[4];
+#pragma unroll
+      for (int cc = 0; cc < 4; ++cc)
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+          pf[cc][t] = (T)pd[cc >> 1][8 * (cc & 1) + t];
+          dsf[cc][t] = (T)s[cc >> 1][8 * (cc & 1) + t];
+        }
+      // dV^T += dO^T P_dropped ;  dK^T += Q^T dS
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc) {
+          const T* gb = Gs + 16 * cc * D;
+          const T* qb_ = Qs + 16 * cc * D;
+          dv[db] = mfma32(tr_frag<T8>(gb + tro.off[db][0], gb + tro.off[db][1]), pf[cc], dv[db]);
+          dk[db] = mfma32(tr_frag<T8>(qb_ + tro.off[db][0], qb_ + tro.off[db][1]), dsf[cc], dk[db]);
+        }
+    }
+    __syncthreads();
+    itile = inext;
+  }
+  store_rows<T, D>((T*)a.dV + head_off + (int64_t)kj * a.sn, dv, DROPOUT ? a.keep_scale : 1.f, g);
+  store_rows<T, D>((T*)a.dK + head_off + (int64_t)kj * a.sn, dk, a.tau, g);
+}
+
+template <typename T, int D>
+int launch_bwd_td(const KArgs& a, bool causal, bool dropout, bool sparse, hipStream_t s) {
+  const int64_t rows = (int64_t)a.B * a.H * a.N;
+  const int64_t threads = rows * (D / 8);
+  hipLaunchKernelGGL((rowdot_kernel<T, D>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, a);
+  int e = (int)hipGetLastError();
+  if (e != 0) return e;
+  const dim3 grid(kXcds * a.chunk), block(NT);
+#define ATTN_BWD_CASE(C, P, S)                                                   \
+  if (causal == C && dropout == P && sparse == S) {                              \
+    hipLaunchKernelGGL((dq_kernel<T, D, C, P, S>), grid, block, 0, s, a);        \
+    e = (int)hipGetLastError();                                                  \
+    if (e != 0) return e;                                                        \
+    hipLaunchKernelGGL((dkv_kernel<T, D, C, P, S>), grid, block, 0, s, a);       \
+    return (int)hipGetLastError();                                               \
+  }
+  ATTN_BWD_CASE(false, false, false)
+  ATTN_BWD_CASE(true, false, false)
+  ATTN_BWD_CASE(false, true, false)
+  ATTN_BWD_CASE(true, true, false)
+  ATTN_BWD_CASE(false, false, true)
+  ATTN_BWD_CASE(true, false, true)
+  ATTN_BWD_CASE(false, true, true)
+  ATTN_BWD_CASE(true, true, true)
+#undef ATTN_BWD_CASE
+  return (int)hipErrorInvalidValue;
+}
+
+}  // namespace
+
+int launch_bwd(const KArgs& a, int dtype, int d, bool causal, bool dropout, bool sparse, hipStream_t s) {
+  if (dtype == 0 && d == 64) return launch_bwd_td<_Float16, 64>(a, causal, dropout, sparse, s);
+  if (dtype == 0 && d == 128) return launch_bwd_td<_Float16, 128>(a, causal, dropout, sparse, s);
+  if (dtype == 1 && d == 64) return launch_bwd_td<__bf16, 64>(a, causal, dropout, sparse, s);
+  if (dtype == 1 && d == 128) return launch_bwd_td<__bf16, 128>(a, causal, dropout, sparse, s);
+  return (int)hipErrorInvalidValue;
+}
+
+}  // namespace attn

@@ -89,6 +89,48 @@ __device__ __forceinline__ int xcd_item(int n_items, int chunk) {
   const int item = (id % kXcds) * chunk + id / kXcds;
   return item < n_items && (id / kXcds) < chunk ? item : -1;
 }
+// XOR swizzle of the 16-byte chunk index inside an unpadded [rows][D] LDS tile.  It makes both
+// access patterns used on the tiles conflict-free on a 64-bank LDS: 16 consecutive rows at one
+// chunk (row-wise 16-byte operand reads) and 4 consecutive rows x 64 bytes (transposing reads).
+template <int D> __device__ __forceinline__ int swz_bits(int row) {
+  if constexpr (D == 128) return ((row & 3) << 2) | ((row >> 2) & 3);
+  else return (((row >> 1) & 1) << 2) | ((row >> 2) & 3);
+}
+template <int D> __device__ __forceinline__ int lds_off(int row, int chunk) {
+  return row * D + ((chunk ^ swz_bits<D>(row)) << 3);
+}
+
+// Iterates, in increasing order, over the 64-wide tiles a workgroup must visit.
+// Dense: first .. limit-1 (in tiles).  Sparse: the two 64-wide halves of every 128-block b in
+// [first, limit) with mask[b * stride] != 0.  All state is wavefront-uniform.
+template <bool SPARSE> struct TileIter {
+  const uint8_t* mask;
+  int64_t stride;
+  int limit, pos, base, half;
+  uint64_t bits;
+  __device__ __forceinline__ void init(const uint8_t* m, int64_t st, int first, int lim) {
+    mask = m; stride = st; limit = lim; pos = first; bits = 0; base = 0; half = -1;
+  }
+  __device__ __forceinline__ int next() {
+    if constexpr (!SPARSE) {
+      return pos < limit ? pos++ : -1;
+    } else {
+      if (half >= 0) { const int t = half; half = -1; return t; }
+      while (bits == 0) {
+        if (pos >= limit) return -1;
+        const int blk = pos + (int)(threadIdx.x & 63);
+        const bool on = blk < limit && mask[(int64_t)blk * stride] != 0;
+        bits = __ballot(on);
+        base = pos;
+        pos += 64;
+      }
+      const int b = __builtin_ctzll(bits);
+      bits &= bits - 1;
+      half = 2 * (base + b) + 1;
+      return 2 * (base + b);
+    }
+  }
+};
 #endif  // __HIPCC__
 
 }  // namespace attn

@@ -30,42 +30,6 @@ template <int D> struct Lds {
   static constexpr int V_ELEMS = BC * VS;
 };
 
-// Iterates over the 64-key tiles this Q tile must visit, in increasing order.
-// Dense: 0 .. n-1.  Sparse: the two 64-key halves of every non-zero 128x128 block of mask row qt.
-// All state is wavefront-uniform.
-template <bool SPARSE> struct TileIter {
-  const uint8_t* row;  // mask row (sparse)
-  int limit;           // number of 128-blocks (sparse) or 64-tiles (dense) to consider
-  int pos;             // dense: next tile; sparse: next 64-block chunk base
-  uint64_t bits;       // sparse: pending blocks of the current chunk
-  int base;            // sparse: block index of bit 0
-  int half;            // sparse: pending second half (tile index) or -1
-  __device__ void init(const uint8_t* mask_row, int lim) {
-    row = mask_row; limit = lim; pos = 0; bits = 0; base = 0; half = -1;
-  }
-  __device__ int next() {
-    if constexpr (!SPARSE) {
-      return pos < limit ? pos++ : -1;
-    } else {
-      if (half >= 0) { const int t = half; half = -1; return t; }
-      while (bits == 0) {
-        if (pos >= limit) return -1;
-        const int lane = threadIdx.x & 63;
-        const int blk = pos + lane;
-        const bool on = blk < limit && row[blk] != 0;
-        bits = __ballot(on);
-        base = pos;
-        pos += 64;
-      }
-      const int b = __builtin_ctzll(bits);
-      bits &= bits - 1;
-      const int blk = base + b;
-      half = 2 * blk + 1;
-      return 2 * blk;
-    }
-  }
-};
-
 template <typename T, int D, bool CAUSAL, bool DROPOUT, bool SPARSE>
 __global__ __launch_bounds__(NT, 2) void fwd_kernel(const KArgs a) {
   typedef typename Vec<T>::x8 T8;
@@ -117,7 +81,7 @@ __global__ __launch_bounds__(NT, 2) void fwd_kernel(const KArgs a) {
     int lim;
     if constexpr (SPARSE) lim = CAUSAL ? qt + 1 : a.T;
     else lim = CAUSAL ? 2 * qt + 2 : a.N / BC;
-    it.init(SPARSE ? a.mask + (int64_t)h * a.mask_sh + (int64_t)qt * a.T : nullptr, lim);
+    it.init(SPARSE ? a.mask + (int64_t)h * a.mask_sh + (int64_t)qt * a.T : nullptr, 1, 0, lim);
   }
 
   // global -> register staging of one K/V tile

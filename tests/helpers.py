@@ -82,3 +82,35 @@ def assert_forward_ok(res):
     # the 16-bit O meets it up to half a unit in the last place of the output type
     assert res["o_excess"] <= FWD_ATOL, res
     assert res["lse"] <= LSE_ATOL, res
+
+
+def check_backward(t, dev, dtype, tau, *, causal=False, p=0.0, seed=0, offset=0, block_mask=None,
+                   heads=None, o_fp32=False):
+    """fwd + bwd through the C ABI; dQ, dK, dV compared per head with the oracle (relative L2)."""
+    B, H, N, d = t["Q"].shape
+    kw = dict(softmax_scale=tau, causal=causal, dropout_p=p, seed=seed, offset=offset, o_fp32=o_fp32)
+    if block_mask is None:
+        O, L = binding.attn_fwd(dev["Q"], dev["K"], dev["V"], **kw)
+        g = binding.attn_bwd(dev["Q"], dev["K"], dev["V"], O, dev["dO"], L, **kw)
+    else:
+        bm = torch.from_numpy(block_mask).cuda()
+        O, L = binding.attn_blocksparse_fwd(dev["Q"], dev["K"], dev["V"], bm, **kw)
+        g = binding.attn_blocksparse_bwd(dev["Q"], dev["K"], dev["V"], O, dev["dO"], L, bm, **kw)
+    torch.cuda.synchronize()
+    g = [to_np(x) for x in g]
+    heads = heads or [(b, h) for b in range(B) for h in range(H)]
+    res = dict(dQ=0.0, dK=0.0, dV=0.0)
+    for b, h in heads:
+        keep = orc.dropout_keep_mask(b, h, H, N, p, seed, offset) if p > 0 else None
+        bm_h = None if block_mask is None else (block_mask if block_mask.ndim == 2 else block_mask[h])
+        ref = orc.backward_head(t["Q"][b, h], t["K"][b, h], t["V"][b, h], t["dO"][b, h], tau,
+                                causal=causal, p_drop=p, keep=keep, block_mask=bm_h)
+        for name, got, want in zip(("dQ", "dK", "dV"), g, ref):
+            assert np.isfinite(got[b, h]).all(), name
+            res[name] = max(res[name], rel_l2(got[b, h], want))
+    return res
+
+
+def assert_backward_ok(res):
+    for name in ("dQ", "dK", "dV"):
+        assert res[name] <= GRAD_REL_L2, res

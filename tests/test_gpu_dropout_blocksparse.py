@@ -1,0 +1,104 @@
+"""Dropout mask bit-exactness, dropout forward parity, and the block-sparse variant."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import attention_oracle as orc
+from tests import helpers as hp
+from paper_2205_14135_amd import binding, inputs
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("B,H,N,p,seed,offset", [
+    (2, 3, 256, 0.1, inputs.BASE_DROPOUT_SEED + 1, 0),
+    (1, 2, 384, 0.5, 0xFEDCBA9876543210, 0x1_0000_0005),
+    (1, 1, 128, 0.9, 1, 0xFFFFFFFF),
+])
+def test_dropout_mask_is_bit_exact(B, H, N, p, seed, offset):
+    keep = binding.attn_debug_dropout_mask(B, H, N, p, seed, offset).cpu().numpy().astype(bool)
+    for b in range(B):
+        for h in range(H):
+            want = orc.dropout_keep_mask(b, h, H, N, p, seed, offset)
+            assert (keep[b, h] == want).all()
+
+
+@pytest.mark.parametrize("dtype,d,causal", [("fp16", 64, False), ("bf16", 64, True), ("bf16", 128, True)])
+def test_forward_with_dropout(dtype, d, causal):
+    t, dev = hp.make_case(2, 2, 384, d, dtype, 400 + d)
+    res = hp.check_forward(t, dev, dtype, 1 / math.sqrt(d), causal=causal, p=0.1,
+                           seed=inputs.BASE_DROPOUT_SEED + 2, offset=9)
+    print("dropout fwd", dtype, d, causal, res)
+    hp.assert_forward_ok(res)
+
+
+def test_kernels_apply_exactly_the_oracle_mask():
+    """Q = 0 makes P uniform, so O_i = (1/((1-p) N)) * sum_{j kept} V_j: with V the N x N identity
+    split over d-wide column slabs, O read back slab by slab IS the keep mask of the kernel."""
+    B, H, N, d, p = 1, 2, 128, 64, 0.3
+    seed, offset = 77, 5
+    Q = torch.zeros((B, H, N, d), dtype=torch.float16, device="cuda")
+    K = torch.zeros_like(Q)
+    want = np.stack([orc.dropout_keep_mask(0, h, H, N, p, seed, offset) for h in range(H)])
+    got = np.zeros((H, N, N), dtype=bool)
+    for slab in range(N // d):
+        V = torch.zeros((B, H, N, d), dtype=torch.float16, device="cuda")
+        idx = torch.arange(d, device="cuda")
+        V[:, :, slab * d + idx, idx] = 1.0
+        O, _ = binding.attn_fwd(Q, K, V, softmax_scale=1.0, dropout_p=p, seed=seed, offset=offset, o_fp32=True)
+        got[:, :, slab * d:(slab + 1) * d] = (O[0] > 0).cpu().numpy()
+    assert (got == want).all()
+
+
+def _random_block_mask(T, seed, density=0.4):
+    rng = np.random.default_rng(seed)
+    m = (rng.random((T, T)) < density).astype(np.uint8)
+    m[np.arange(T), np.arange(T)] = 1
+    return m
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_blocksparse_butterfly_small(d):
+    T = 8
+    N = 128 * T
+    t, dev = hp.make_case(1, 2, N, d, "bf16", 500 + d)
+    bm = inputs.butterfly_block_mask(T)
+    res = hp.check_forward(t, dev, "bf16", 1 / math.sqrt(d), block_mask=bm)
+    print("butterfly fwd", d, res)
+    hp.assert_forward_ok(res)
+    resb = hp.check_backward(t, dev, "bf16", 1 / math.sqrt(d), block_mask=bm)
+    print("butterfly bwd", d, resb)
+    hp.assert_backward_ok(resb)
+
+
+def test_blocksparse_random_per_head_mask_causal_dropout_and_empty_rows():
+    T = 5
+    N = 128 * T
+    H = 2
+    t, dev = hp.make_case(1, H, N, 64, "fp16", 600)
+    bm = np.stack([_random_block_mask(T, 1), _random_block_mask(T, 2)])
+    bm[1, 3, :] = 0          # a query block that sees nothing: O = 0, LSE = -inf, zero gradients
+    kw = dict(causal=True, p=0.2, seed=9, offset=1, block_mask=bm)
+    res = hp.check_forward(t, dev, "fp16", 0.125, **kw)
+    print("sparse fwd", res)
+    hp.assert_forward_ok(res)
+    resb = hp.check_backward(t, dev, "fp16", 0.125, **kw)
+    print("sparse bwd", resb)
+    hp.assert_backward_ok(resb)
+
+
+def test_blocksparse_all_ones_equals_dense_bitwise():
+    T = 3
+    t, dev = hp.make_case(1, 2, 128 * T, 128, "bf16", 700)
+    kw = dict(softmax_scale=0.09, causal=True, dropout_p=0.1, seed=4)
+    ones = torch.ones((T, T), dtype=torch.uint8, device="cuda")
+    O, L = binding.attn_fwd(dev["Q"], dev["K"], dev["V"], **kw)
+    Os, Ls = binding.attn_blocksparse_fwd(dev["Q"], dev["K"], dev["V"], ones, **kw)
+    g = binding.attn_bwd(dev["Q"], dev["K"], dev["V"], O, dev["dO"], L, **kw)
+    gs = binding.attn_blocksparse_bwd(dev["Q"], dev["K"], dev["V"], Os, dev["dO"], Ls, ones, **kw)
+    torch.cuda.synchronize()
+    assert torch.equal(O, Os) and torch.equal(L, Ls)
+    for a, b in zip(g, gs):
+        assert torch.equal(a, b)

@@ -1,0 +1,111 @@
+"""Host-side checks that need no GPU: the library loads, exports every declared symbol,
+and rejects bad arguments before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2205_14135_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2205_14135_amd import build
+        build.build()
+    return binding.load()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "attn.h")).read()
+    declared = set(re.findall(r"\b(attn_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(binding.SYMBOLS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_version_and_strerror(lib):
+    assert binding.version() >= 100
+    assert binding.strerror(0) == "ok"
+    texts = {binding.strerror(-i) for i in range(1, 10)}
+    assert len(texts) == 9 and "unknown status" not in texts
+    assert binding.strerror(-99) == "unknown status"
+
+
+def _params(**kw):
+    p = binding.AttnParams()
+    p.B, p.H, p.N, p.d = 1, 1, 128, 64
+    p.dtype = binding.ATTN_BF16
+    p.softmax_scale = 0.125
+    for k, v in kw.items():
+        setattr(p, k, v)
+    return p
+
+
+def _fwd(lib, p, ptr=0x1000):
+    v = ctypes.c_void_p(ptr)
+    return lib.attn_fwd(ctypes.byref(p), v, v, v, v, v)
+
+
+def test_struct_layout_matches_c():
+    # int32 x5, pad, int64 x3, float, int32, float, pad, uint64 x2, int32, pad, pointer
+    assert ctypes.sizeof(binding.AttnParams) == 96
+    assert binding.AttnParams.stride_b.offset == 24
+    assert binding.AttnParams.seed.offset == 64
+    assert binding.AttnParams.stream.offset == 88
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(dtype=2), -3),
+    (dict(d=96), -4),
+    (dict(d=32), -4),
+    (dict(N=100), -2),
+    (dict(N=0), -2),
+    (dict(B=0), -2),
+    (dict(stride_b=8192, stride_h=8192, stride_n=60), -2),
+    (dict(stride_b=8192, stride_h=8192, stride_n=68), -2),
+    (dict(dropout_p=1.0), -5),
+    (dict(dropout_p=-0.1), -5),
+    (dict(dropout_p=float("nan")), -5),
+    (dict(softmax_scale=0.0), -6),
+    (dict(softmax_scale=-1.0), -6),
+    (dict(softmax_scale=float("inf")), -6),
+    (dict(softmax_scale=float("nan")), -6),
+])
+def test_bad_params_are_rejected_before_launch(lib, kw, code):
+    assert _fwd(lib, _params(**kw)) == code
+
+
+def test_null_pointers_and_workspace(lib):
+    p = _params()
+    assert lib.attn_fwd(None, None, None, None, None, None) == -1
+    assert _fwd(lib, p, ptr=0) == -1
+    v, z = ctypes.c_void_p(0x1000), ctypes.c_void_p(0)
+    need = lib.attn_bwd_workspace_bytes(ctypes.byref(p))
+    assert need == 512 and need % 256 == 0
+    args = [v] * 9
+    assert lib.attn_bwd(ctypes.byref(p), *args, z, need) == -7                      # NULL workspace
+    assert lib.attn_bwd(ctypes.byref(p), *args, ctypes.c_void_p(0x1010), need) == -7  # misaligned
+    assert lib.attn_bwd(ctypes.byref(p), *args, v, need - 1) == -7                  # too small
+    assert lib.attn_bwd(ctypes.byref(p), *([v] * 8 + [z]), v, need) == -1
+    assert lib.attn_bwd_workspace_bytes(ctypes.byref(_params(d=7))) == 0
+
+
+def test_mask_arguments(lib):
+    p = _params(N=256)
+    v, z = ctypes.c_void_p(0x1000), ctypes.c_void_p(0)
+    assert lib.attn_blocksparse_fwd(ctypes.byref(p), z, 128, 0, v, v, v, v, v) == -1
+    assert lib.attn_blocksparse_fwd(ctypes.byref(p), v, 64, 0, v, v, v, v, v) == -8
+    assert lib.attn_blocksparse_fwd(ctypes.byref(p), v, 128, 3, v, v, v, v, v) == -8
+    assert lib.attn_blocksparse_fwd(ctypes.byref(p), v, 128, -4, v, v, v, v, v) == -8
+    assert lib.attn_debug_dropout_mask(ctypes.byref(p), z) == -1
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(FileNotFoundError):
+        binding.load()
