@@ -1,0 +1,298 @@
+#!/usr/bin/env python3
+"""Benchmark of the attention hot path on one MI355X.
+
+A "step" is one forward + one backward pass (attn_fwd, then attn_bwd) over one batch of the
+workload.  Default workload: the d=128, N=4096 point of the sequence-length sweep (B*N = 16384
+tokens, H=16, bf16, non-causal, no dropout).  Prints ONE JSON line:
+
+  value     fwd+bwd TFLOP/s with FLOPs counted as 4*B*H*N^2*d (forward) + 2.5x that (backward),
+            halved under a causal mask, kept blocks only for the block-sparse workloads;
+  roofline  the dominant kernel of the step against the MI355X dense bf16/fp16 MFMA peak,
+            its duration measured with HIP events recorded on the launch stream;
+  cpu_baseline  the fp64 oracle timed on this machine's host cores on a bounded sample.
+
+Other workloads (--workload) exist for profiling and for the sweep table (--sweep).
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_TFLOPS = {"bf16": 2500.0, "fp16": 2500.0}   # MI355X dense MFMA peak
+
+
+def workloads():
+    w = {}
+    for n in (128, 256, 512, 1024, 2048, 4096, 8192, 16384):
+        for d in (64, 128):
+            for causal in (False, True):
+                name = f"sweep_N{n}_d{d}" + ("_causal" if causal else "")
+                w[name] = dict(B=16384 // n, H=16, N=n, d=d, dtype="bf16", causal=causal, p=0.0, sparse=False)
+    w["bert_large"] = dict(B=16, H=16, N=512, d=64, dtype="fp16", causal=False, p=0.1, sparse=False)
+    w["gpt2_medium"] = dict(B=8, H=16, N=1024, d=64, dtype="bf16", causal=True, p=0.1, sparse=False)
+    w["gpt2_medium_d128"] = dict(B=8, H=8, N=1024, d=128, dtype="bf16", causal=True, p=0.1, sparse=False)
+    w["blocksparse_N16384"] = dict(B=1, H=8, N=16384, d=64, dtype="bf16", causal=False, p=0.0, sparse=True)
+    w["blocksparse_N65536"] = dict(B=1, H=8, N=65536, d=64, dtype="bf16", causal=False, p=0.0, sparse=True)
+    return w
+
+
+DEFAULT_WORKLOAD = "sweep_N4096_d128"
+
+
+class HipEvents:
+    """hipEvent_t handles through the HIP runtime's C API (timing on the launch stream)."""
+
+    def __init__(self):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.all = []
+
+    def new(self) -> int:
+        e = ctypes.c_void_p()
+        rc = self.hip.hipEventCreate(ctypes.byref(e))
+        if rc != 0:
+            raise RuntimeError(f"hipEventCreate failed: {rc}")
+        self.all.append(e.value)
+        return e.value
+
+    def record(self, ev: int, stream: int):
+        rc = self.hip.hipEventRecord(ctypes.c_void_p(ev), ctypes.c_void_p(stream))
+        if rc != 0:
+            raise RuntimeError(f"hipEventRecord failed: {rc}")
+
+    def elapsed_ms(self, a: int, b: int) -> float:
+        self.hip.hipEventSynchronize(ctypes.c_void_p(b))
+        ms = ctypes.c_float()
+        rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), ctypes.c_void_p(a), ctypes.c_void_p(b))
+        if rc != 0:
+            raise RuntimeError(f"hipEventElapsedTime failed: {rc}")
+        return float(ms.value)
+
+    def close(self):
+        for e in self.all:
+            self.hip.hipEventDestroy(ctypes.c_void_p(e))
+        self.all = []
+
+
+def flops_fwd(cfg, nnz_blocks=None):
+    if cfg["sparse"]:
+        return 4.0 * cfg["B"] * cfg["H"] * nnz_blocks * 128 * 128 * cfg["d"]
+    f = 4.0 * cfg["B"] * cfg["H"] * cfg["N"] ** 2 * cfg["d"]
+    return f * (0.5 if cfg["causal"] else 1.0)
+
+
+def run_gpu(cfg, steps, warmup, seed):
+    import numpy as np
+    import torch
+    from paper_2205_14135_amd import binding, inputs
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    B, H, N, d = cfg["B"], cfg["H"], cfg["N"], cfg["d"]
+    t = inputs.gaussian_tensors(B, H, N, d, cfg["dtype"], seed)
+    g = {k: inputs.to_torch(v, cfg["dtype"], dev) for k, v in t.items()}
+    tau = 1.0 / math.sqrt(d)
+    kw = dict(softmax_scale=tau, causal=cfg["causal"], dropout_p=cfg["p"],
+              seed=inputs.BASE_DROPOUT_SEED, offset=0)
+    bm = bm_np = None
+    nnz = None
+    if cfg["sparse"]:
+        bm_np = inputs.butterfly_block_mask(N // 128)
+        bm = torch.from_numpy(bm_np).to(dev)
+        nnz = int(bm_np.sum())
+    O = torch.empty_like(g["Q"])
+    L = torch.empty((B, H, N), dtype=torch.float32, device=dev)
+    grads = tuple(torch.empty_like(g["Q"]) for _ in range(3))
+    ws = torch.empty(max(256, binding.attn_bwd_workspace_bytes(binding.make_params(g["Q"], tau))),
+                     dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream(dev).cuda_stream
+    hev = HipEvents()
+
+    def fwd():
+        if bm is None:
+            binding.attn_fwd(g["Q"], g["K"], g["V"], out=O, lse=L, **kw)
+        else:
+            binding.attn_blocksparse_fwd(g["Q"], g["K"], g["V"], bm, out=O, lse=L, **kw)
+
+    def bwd(events):
+        binding.attn_bwd_timed(g["Q"], g["K"], g["V"], O, g["dO"], L, events, block_mask=bm,
+                               grads=grads, workspace=ws, **kw)
+
+    scratch_ev = [hev.new() for _ in range(4)]
+    for _ in range(warmup):
+        fwd()
+        bwd(scratch_ev)
+    torch.cuda.synchronize()
+    evs = [[hev.new() for _ in range(5)] for _ in range(steps)]   # f0, f1=b0, b1, b2, b3
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(steps):
+        e = evs[s]
+        hev.record(e[0], stream)
+        fwd()
+        bwd(e[1:5])
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    names = ["fwd_kernel", "rowdot_kernel", "dq_kernel", "dkv_kernel"]
+    dur = {n: 0.0 for n in names}
+    for e in evs:
+        for i, n in enumerate(names):
+            dur[n] += hev.elapsed_ms(e[i], e[i + 1])
+    dur = {n: v / steps for n, v in dur.items()}
+    hev.close()
+    return dict(ms_per_step=wall_ms / steps, kernel_ms=dur, nnz=nnz, tensors=t, block_mask=bm_np, tau=tau)
+
+
+def cpu_baseline(cfg, run, budget_s=12.0, max_s=30.0):
+    """Times the fp64 oracle (forward + backward of whole heads) on the host cores."""
+    import numpy as np
+    from oracle import attention_oracle as orc
+    from paper_2205_14135_amd import inputs
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    t, tau = run["tensors"], run["tau"]
+    B, H, N, d = cfg["B"], cfg["H"], cfg["N"], cfg["d"]
+    chunk = 2048 if N > 8192 else N      # row chunks keep the N x N temporaries in memory
+    heads_done, partial = 0, 0.0
+    t0 = time.perf_counter()
+    for b, h in [(b, h) for b in range(B) for h in range(H)]:
+        q, k, v, do = (t[n][b, h].astype(np.float64) for n in ("Q", "K", "V", "dO"))
+        aborted = False
+        for r0 in range(0, N, chunk):
+            rows = np.arange(r0, min(N, r0 + chunk))
+            keep = (orc.dropout_keep_mask(b, h, H, N, cfg["p"], inputs.BASE_DROPOUT_SEED, 0, rows=rows)
+                    if cfg["p"] > 0 else None)
+            kws = dict(causal=cfg["causal"], p_drop=cfg["p"], keep=keep, block_mask=run["block_mask"], rows=rows)
+            orc.forward_head(q, k, v, tau, **kws)
+            orc.backward_head(q, k, v, do, tau, **kws)
+            partial = min(1.0, (r0 + chunk) / N)
+            if time.perf_counter() - t0 > max_s and partial < 1.0:
+                aborted = True
+                break
+        if aborted:
+            break
+        heads_done += 1
+        if time.perf_counter() - t0 > budget_s:
+            break
+    el = time.perf_counter() - t0
+    if heads_done == 0:
+        per_head = el / partial
+        sample = f"{partial:.3f} of head (0,0) in row chunks of {chunk}, extrapolated to one head"
+    else:
+        per_head = el / heads_done
+        sample = f"{heads_done} of {B * H} heads, forward+backward each"
+    nnz = run["nnz"]
+    fl_head = 3.5 * flops_fwd(cfg, nnz) / (B * H)
+    return dict(value=fl_head / per_head * 1e-12, unit="TFLOP/s", cores=int(threads), kind="oracle",
+                sample=sample, seconds=round(el, 2))
+
+
+def load_traffic(workload, kernel):
+    """HBM bytes per launch from committed rocprofv3 counter runs, if recorded for this workload."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if not os.path.exists(path):
+        return None
+    try:
+        with open(path) as f:
+            tab = json.load(f)
+        return tab.get(workload, {}).get(kernel)
+    except Exception:
+        return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep", action="store_true", help="also time every sweep point (extra JSON lines on stderr)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU; every (batch, head) problem is independent, so N GPUs "
+              "would each take B*H/N heads with no communication. Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    wl = workloads()
+    if args.workload not in wl:
+        print("unknown workload; choose from: " + ", ".join(sorted(wl)), file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(1)
+    from paper_2205_14135_amd import binding, inputs
+    binding.load()
+
+    if args.sweep:
+        for name in sorted(wl):
+            c = wl[name]
+            r = run_gpu(c, max(3, args.steps // 3), 2, inputs.BASE_SEED + 3)
+            f = flops_fwd(c, r["nnz"])
+            k = r["kernel_ms"]
+            bwd_ms = k["rowdot_kernel"] + k["dq_kernel"] + k["dkv_kernel"]
+            print(json.dumps(dict(workload=name, fwd_ms=round(k["fwd_kernel"], 4), bwd_ms=round(bwd_ms, 4),
+                                  fwd_tflops=round(f / k["fwd_kernel"] * 1e-9, 1),
+                                  bwd_tflops=round(2.5 * f / bwd_ms * 1e-9, 1),
+                                  fwd_bwd_tflops=round(3.5 * f / (k["fwd_kernel"] + bwd_ms) * 1e-9, 1))),
+                  file=sys.stderr, flush=True)
+
+    cfg = wl[args.workload]
+    run = run_gpu(cfg, args.steps, args.warmup, inputs.BASE_SEED + 3)
+    f_fwd = flops_fwd(cfg, run["nnz"])
+    total = 3.5 * f_fwd
+    value = total / run["ms_per_step"] * 1e-9
+    kms = run["kernel_ms"]
+    # algorithmic FLOPs of each launch: forward two tile products; dK/dV kernel four of the five
+    # backward products (S, dP, dV, dK); dQ kernel one (its S and dP are recomputation)
+    algo = {"fwd_kernel": f_fwd, "dq_kernel": 0.5 * f_fwd, "dkv_kernel": 2.0 * f_fwd}
+    dominant = max(algo, key=lambda n: kms[n])
+    achieved = algo[dominant] / kms[dominant] * 1e-9
+    peak = PEAK_TFLOPS[cfg["dtype"]]
+    out = {
+        "metric": "attention fwd+bwd TFLOP/s",
+        "value": round(value, 2),
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(run["ms_per_step"], 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": cfg["dtype"],
+        "data": "synthetic",
+        "config": {"workload": args.workload, **{k: cfg[k] for k in ("B", "H", "N", "d", "causal", "p", "sparse")}},
+        "frac_of_mfma_peak": round(value / peak, 4),
+        "roofline": {
+            "bound": "mfma", "kernel": dominant, "achieved": round(achieved, 2), "peak": peak,
+            "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
+            "traffic": load_traffic(args.workload, dominant),
+            "avg_ms": round(kms[dominant], 4),
+        },
+        "kernels": {n: {"avg_ms": round(v, 4),
+                        "algorithmic_tflops": (round(algo[n] / v * 1e-9, 1) if n in algo else None)}
+                    for n, v in kms.items()},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, run)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

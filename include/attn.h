@@ -141,6 +141,19 @@ int attn_blocksparse_bwd(const attn_params* p, const uint8_t* block_mask, int32_
                          void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes);
 
 /*
+ * Profiling aid for the backward pass (Algorithm 4 as attn_bwd / attn_blocksparse_bwd run it):
+ * identical to attn_bwd when block_mask is NULL and to attn_blocksparse_bwd otherwise, and in
+ * addition records the caller's four hipEvent_t handles on p->stream: events[0] before the first
+ * launch, events[1] after the row-dot kernel (D = rowsum(dO o O)), events[2] after the dQ kernel,
+ * events[3] after the dK/dV kernel.  The events stay owned by the caller.
+ */
+int attn_bwd_timed(const attn_params* p, const uint8_t* block_mask, int32_t mask_block,
+                   int64_t mask_stride_h, const void* Q, const void* K, const void* V,
+                   const void* O, const void* dO, const float* LSE,
+                   void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes,
+                   void* const* events);
+
+/*
  * Test hook: writes the dropout keep mask the kernels use, keep[b][h][i][j] in
  * {0, 1}, as a packed device uint8 [B,H,N,N] array (N*N bytes per head: only
  * for small problems).  Uses B, H, N, dropout_p, seed, offset, stream of p.

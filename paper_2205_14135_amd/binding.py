@@ -19,7 +19,8 @@ ATTN_FP16, ATTN_BF16 = 0, 1
 
 SYMBOLS = (
     "attn_fwd", "attn_bwd_workspace_bytes", "attn_bwd", "attn_blocksparse_fwd",
-    "attn_blocksparse_bwd", "attn_debug_dropout_mask", "attn_strerror", "attn_version",
+    "attn_blocksparse_bwd", "attn_bwd_timed", "attn_debug_dropout_mask", "attn_strerror",
+    "attn_version",
 )
 
 
@@ -68,6 +69,8 @@ def load() -> ctypes.CDLL:
     lib.attn_blocksparse_fwd.restype = ctypes.c_int
     lib.attn_blocksparse_bwd.argtypes = [P, vp, i32, i64] + [vp] * 9 + [vp, sz]
     lib.attn_blocksparse_bwd.restype = ctypes.c_int
+    lib.attn_bwd_timed.argtypes = [P, vp, i32, i64] + [vp] * 9 + [vp, sz, ctypes.POINTER(vp)]
+    lib.attn_bwd_timed.restype = ctypes.c_int
     lib.attn_debug_dropout_mask.argtypes = [P, vp]
     lib.attn_debug_dropout_mask.restype = ctypes.c_int
     lib.attn_strerror.argtypes = [ctypes.c_int]
@@ -214,6 +217,27 @@ def attn_blocksparse_bwd(Q, K, V, O, dO, LSE, block_mask, *, softmax_scale, mask
                                        _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE),
                                        _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(workspace), nbytes),
            "attn_blocksparse_bwd")
+    return dQ, dK, dV
+
+
+def attn_bwd_timed(Q, K, V, O, dO, LSE, events, *, softmax_scale, block_mask=None, mask_block=128,
+                   causal=False, dropout_p=0.0, seed=0, offset=0, o_fp32=False, workspace=None,
+                   grads=None, stream=None):
+    """attn_bwd / attn_blocksparse_bwd that also records four caller-owned hipEvent_t handles
+    (ints) on the stream: before, after row-dot, after dQ, after dK/dV."""
+    _same_layout(Q, K, V, dO)
+    p = make_params(Q, softmax_scale, causal, dropout_p, seed, offset, o_fp32, stream)
+    msh = 0 if block_mask is None else _mask_args(block_mask, Q.shape[1])
+    if grads is None:
+        grads = tuple(torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device)
+                      for _ in range(3))
+    dQ, dK, dV = grads
+    workspace, nbytes = _workspace(p, Q.device, workspace)
+    ev = (ctypes.c_void_p * 4)(*[ctypes.c_void_p(int(e)) for e in events])
+    _check(load().attn_bwd_timed(ctypes.byref(p), _ptr(block_mask), int(mask_block), int(msh),
+                                 _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE),
+                                 _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(workspace), nbytes, ev),
+           "attn_bwd_timed")
     return dQ, dK, dV
 
 

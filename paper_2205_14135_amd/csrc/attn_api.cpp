@@ -9,6 +9,8 @@ namespace {
 
 constexpr int kVersion = 100;  // 0.1.0
 
+static_assert(sizeof(attn_params) == 96, "attn_params layout is part of the ABI");
+
 struct Checked {
   attn::KArgs k;
   int dtype, d;
@@ -86,7 +88,8 @@ int fwd_common(const attn_params* p, const uint8_t* mask, int64_t mask_sh, bool 
 
 int bwd_common(const attn_params* p, const uint8_t* mask, int64_t mask_sh, bool sparse,
                const void* Q, const void* K, const void* V, const void* O, const void* dO,
-               const float* LSE, void* dQ, void* dK, void* dV, void* ws, size_t ws_bytes) {
+               const float* LSE, void* dQ, void* dK, void* dV, void* ws, size_t ws_bytes,
+               void* const* events = nullptr) {
   Checked c;
   const int st = check_params(p, &c);
   if (st != ATTN_OK) return st;
@@ -98,7 +101,15 @@ int bwd_common(const attn_params* p, const uint8_t* mask, int64_t mask_sh, bool 
   c.k.Dvec = (float*)ws;
   c.k.mask = mask; c.k.mask_sh = mask_sh;
   set_items(c.k, c.k.N / 128);
-  const int e = attn::launch_bwd(c.k, c.dtype, c.d, c.causal, c.dropout, sparse, c.stream);
+  hipEvent_t ev[4];
+  if (events) {
+    for (int i = 0; i < 4; ++i) {
+      if (events[i] == nullptr) return ATTN_ERR_NULL;
+      ev[i] = (hipEvent_t)events[i];
+    }
+  }
+  const int e = attn::launch_bwd(c.k, c.dtype, c.d, c.causal, c.dropout, sparse, c.stream,
+                                 events ? ev : nullptr);
   return e == 0 ? ATTN_OK : ATTN_ERR_LAUNCH;
 }
 
@@ -145,6 +156,22 @@ int attn_blocksparse_bwd(const attn_params* p, const uint8_t* block_mask, int32_
   if (st != ATTN_OK) return st;
   return bwd_common(p, block_mask, mask_stride_h, true, Q, K, V, O, dO, LSE, dQ, dK, dV, workspace,
                     workspace_bytes);
+}
+
+int attn_bwd_timed(const attn_params* p, const uint8_t* block_mask, int32_t mask_block,
+                   int64_t mask_stride_h, const void* Q, const void* K, const void* V, const void* O,
+                   const void* dO, const float* LSE, void* dQ, void* dK, void* dV, void* workspace,
+                   size_t workspace_bytes, void* const* events) {
+  if (events == nullptr) return ATTN_ERR_NULL;
+  if (block_mask != nullptr) {
+    Checked c;
+    int st = check_params(p, &c);
+    if (st != ATTN_OK) return st;
+    st = check_mask(block_mask, mask_block, mask_stride_h, p);
+    if (st != ATTN_OK) return st;
+  }
+  return bwd_common(p, block_mask, mask_stride_h, block_mask != nullptr, Q, K, V, O, dO, LSE, dQ, dK, dV,
+                    workspace, workspace_bytes, events);
 }
 
 int attn_debug_dropout_mask(const attn_params* p, uint8_t* keep) {

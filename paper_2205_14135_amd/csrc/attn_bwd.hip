@@ -384,20 +384,25 @@ __global__ __launch_bounds__(NT, 1) void dkv_kernel(const KArgs a) {
 }
 
 template <typename T, int D>
-int launch_bwd_td(const KArgs& a, bool causal, bool dropout, bool sparse, hipStream_t s) {
+int launch_bwd_td(const KArgs& a, bool causal, bool dropout, bool sparse, hipStream_t s, hipEvent_t* ev) {
   const int64_t rows = (int64_t)a.B * a.H * a.N;
   const int64_t threads = rows * (D / 8);
+  if (ev) (void)hipEventRecord(ev[0], s);
   hipLaunchKernelGGL((rowdot_kernel<T, D>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, a);
   int e = (int)hipGetLastError();
   if (e != 0) return e;
+  if (ev) (void)hipEventRecord(ev[1], s);
   const dim3 grid(kXcds * a.chunk), block(NT);
 #define ATTN_BWD_CASE(C, P, S)                                                   \
   if (causal == C && dropout == P && sparse == S) {                              \
     hipLaunchKernelGGL((dq_kernel<T, D, C, P, S>), grid, block, 0, s, a);        \
     e = (int)hipGetLastError();                                                  \
     if (e != 0) return e;                                                        \
+    if (ev) (void)hipEventRecord(ev[2], s);                                      \
     hipLaunchKernelGGL((dkv_kernel<T, D, C, P, S>), grid, block, 0, s, a);       \
-    return (int)hipGetLastError();                                               \
+    e = (int)hipGetLastError();                                                  \
+    if (ev) (void)hipEventRecord(ev[3], s);                                      \
+    return e;                                                                    \
   }
   ATTN_BWD_CASE(false, false, false)
   ATTN_BWD_CASE(true, false, false)
@@ -413,11 +418,12 @@ int launch_bwd_td(const KArgs& a, bool causal, bool dropout, bool sparse, hipStr
 
 }  // namespace
 
-int launch_bwd(const KArgs& a, int dtype, int d, bool causal, bool dropout, bool sparse, hipStream_t s) {
-  if (dtype == 0 && d == 64) return launch_bwd_td<_Float16, 64>(a, causal, dropout, sparse, s);
-  if (dtype == 0 && d == 128) return launch_bwd_td<_Float16, 128>(a, causal, dropout, sparse, s);
-  if (dtype == 1 && d == 64) return launch_bwd_td<__bf16, 64>(a, causal, dropout, sparse, s);
-  if (dtype == 1 && d == 128) return launch_bwd_td<__bf16, 128>(a, causal, dropout, sparse, s);
+int launch_bwd(const KArgs& a, int dtype, int d, bool causal, bool dropout, bool sparse, hipStream_t s,
+               hipEvent_t* ev) {
+  if (dtype == 0 && d == 64) return launch_bwd_td<_Float16, 64>(a, causal, dropout, sparse, s, ev);
+  if (dtype == 0 && d == 128) return launch_bwd_td<_Float16, 128>(a, causal, dropout, sparse, s, ev);
+  if (dtype == 1 && d == 64) return launch_bwd_td<__bf16, 64>(a, causal, dropout, sparse, s, ev);
+  if (dtype == 1 && d == 128) return launch_bwd_td<__bf16, 128>(a, causal, dropout, sparse, s, ev);
   return (int)hipErrorInvalidValue;
 }
 

@@ -41,7 +41,9 @@ enum { kXcds = 8, kMaskBlock = 128 };
 
 // Launchers (defined in the .hip files).  dtype: 0 fp16, 1 bf16.  Return hipError_t as int.
 int launch_fwd(const KArgs& a, int dtype, int d, bool causal, bool dropout, bool sparse, hipStream_t s);
-int launch_bwd(const KArgs& a, int dtype, int d, bool causal, bool dropout, bool sparse, hipStream_t s);
+// ev: nullptr, or four events recorded before / between / after the three launches.
+int launch_bwd(const KArgs& a, int dtype, int d, bool causal, bool dropout, bool sparse, hipStream_t s,
+               hipEvent_t* ev);
 int launch_dropout_mask(const KArgs& a, uint8_t* keep, hipStream_t s);
 
 #if defined(__HIPCC__)
