@@ -16,6 +16,8 @@
 // V^T fragments come from the row-major V tile in LDS through the gfx950 transposing LDS read.
 #include "attn_common.h"
 
+#include <cstdlib>
+
 namespace attn {
 namespace {
 
@@ -279,6 +281,21 @@ __global__ void dropout_mask_kernel(const KArgs a, uint8_t* keep) {
 }  // namespace
 
 int launch_fwd(const KArgs& a, int dtype, int d, bool causal, bool dropout, bool sparse, hipStream_t s) {
+  // Dense problems take the ping-pong kernel (attn_fwd_pp.hip) where it measured faster on
+  // MI355X: long sequences, where its 256-row workgroups still fill the chip and the MFMA /
+  // softmax overlap pays; short ones keep the 4-wavefront kernel of this file, and so do all
+  // block-sparse problems.  ATTN_FWD_VARIANT=base|pp overrides the choice (bench-time comparison).
+  static const char variant = [] {
+    const char* v = getenv("ATTN_FWD_VARIANT");
+    return v != nullptr ? v[0] : 'a';
+  }();
+  bool use_pp;
+  if (dropout) use_pp = d == 128;
+  else if (d == 128) use_pp = a.N >= (causal ? 4096 : 512);
+  else use_pp = a.N >= (causal ? 8192 : 2048);
+  if (variant == 'b') use_pp = false;
+  if (variant == 'p') use_pp = true;
+  if (!sparse && use_pp) return launch_fwd_pp(a, dtype, d, causal, dropout, s);
   if (dtype == 0 && d == 64) return launch_fwd_td<_Float16, 64>(a, causal, dropout, sparse, s);
   if (dtype == 0 && d == 128) return launch_fwd_td<_Float16, 128>(a, causal, dropout, sparse, s);
   if (dtype == 1 && d == 64) return launch_fwd_td<__bf16, 64>(a, causal, dropout, sparse, s);

@@ -1,0 +1,295 @@
+// Forward pass, dense (no block mask) variant with two wavefront groups in ping-pong.
+//
+// Same arithmetic and register layout as fwd_kernel in attn_fwd.hip (Algorithm 2 of the paper,
+// Q-outer, S^T = K Q^T orientation).  What changes is the schedule.  Per 64-key tile a wavefront
+// alternates between a matrix block M(j) = { O^T += V(j-1)^T P(j-1)^T ; S(j)^T = K(j) Q^T } and a
+// vector block X(j) = { online softmax of tile j }, of roughly equal length.  Two wavefronts that
+// share a SIMD and run the same code drift into the same block and then fight for the same
+// unit, so here a workgroup has 8 wavefronts = 2 groups x 4 SIMDs, each group owning 128 of the
+// workgroup's 256 query rows, and workgroup barriers keep group B exactly one block behind
+// group A: while one group issues MFMA the other issues the softmax VALU work.
+//
+// K and V tiles are double buffered in LDS and shared by both groups.  In global slot numbers
+// (slot 2j: A in M(j), B in X(j-1); slot 2j+1: A in X(j), B in M(j)) K(t) is read in slots
+// 2t, 2t+1 and V(t) in slots 2t+2, 2t+3, so K(t) may be written in slots 2t-2, 2t-1 and V(t) in
+// slots 2t, 2t+1.  Every wavefront stages 1/8 of each tile (global -> registers -> LDS): it stores
+// its share of K(j+1) and V(j) at the start of its own M(j), inside both windows for either group.
+#include "attn_common.h"
+
+namespace attn {
+namespace {
+
+constexpr int BRW = 256;  // query rows per workgroup
+constexpr int BC = 64;    // keys per tile
+constexpr int NT = 512;
+
+template <typename T, int D, bool CAUSAL, bool DROPOUT>
+__global__ __launch_bounds__(NT) void fwd_pp_kernel(const KArgs a) {
+  typedef typename Vec<T>::x8 T8;
+  typedef typename Vec<T>::x4 T4;
+  constexpr int KS = D + 8, VS = D + 32;  // padded row strides, as in fwd_kernel
+  constexpr int KK = D / 16, DB = D / 32;
+  constexpr int CPR = D / 8, RPP = NT / CPR, NP = BC / RPP;
+
+  __shared__ __attribute__((aligned(16))) T Ks[2][BC * KS];
+  __shared__ __attribute__((aligned(16))) T Vs[2][BC * VS];
+
+  const int item = xcd_item(a.n_items, a.chunk);
+  if (item < 0) return;
+  const int n_qt = (a.N + BRW - 1) / BRW;
+  const int bh = item / n_qt;
+  const int qt = CAUSAL ? (n_qt - 1 - item % n_qt) : item % n_qt;
+  const int b = bh / a.H, h = bh % a.H;
+  const int64_t head_off = (int64_t)b * a.sb + (int64_t)h * a.sh;
+  const T* __restrict__ Qg = (const T*)a.Q + head_off;
+  const T* __restrict__ Kg = (const T*)a.K + head_off;
+  const T* __restrict__ Vg = (const T*)a.V + head_off;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const bool group_b = wave >= 4;
+  const int r = lane & 31, g = lane >> 5;
+  const int q0 = qt * BRW + wave * 32;
+  const bool valid = q0 < a.N;          // N is a multiple of 128: whole wavefronts are in or out
+  const int qi = valid ? q0 + r : 0;
+
+  T8 qf[KK];
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk)
+    qf[kk] = *(const T8*)(Qg + (int64_t)qi * a.sn + 16 * kk + 8 * g);
+
+  f32x16 o[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+
+  const int n_tiles = a.N / BC;
+  const int J = CAUSAL ? min(n_tiles, 4 * (qt + 1)) : n_tiles;
+
+  const int lrow = tid / CPR, lchunk = tid % CPR;
+  T8 kreg[NP], vreg[NP];
+  const T* const k_thr = Kg + (int64_t)lrow * a.sn + 8 * lchunk;   // per-thread base; tile offsets are uniform
+  const T* const v_thr = Vg + (int64_t)lrow * a.sn + 8 * lchunk;
+  auto gload_k = [&](int jt) {
+#pragma unroll
+    for (int p = 0; p < NP; ++p) kreg[p] = *(const T8*)(k_thr + (int64_t)(jt * BC + p * RPP) * a.sn);
+  };
+  auto gload_v = [&](int jt) {
+#pragma unroll
+    for (int p = 0; p < NP; ++p) vreg[p] = *(const T8*)(v_thr + (int64_t)(jt * BC + p * RPP) * a.sn);
+  };
+  auto sstore_k = [&](int buf) {
+#pragma unroll
+    for (int p = 0; p < NP; ++p) *(T8*)(&Ks[buf][(p * RPP + lrow) * KS + 8 * lchunk]) = kreg[p];
+  };
+  auto sstore_v = [&](int buf) {
+#pragma unroll
+    for (int p = 0; p < NP; ++p) *(T8*)(&Vs[buf][(p * RPP + lrow) * VS + 8 * lchunk]) = vreg[p];
+  };
+
+  const int i16 = lane & 15, q16 = lane >> 4;
+  const int v_lane_off = (4 * g + (i16 >> 2)) * VS + 16 * (q16 & 1) + 4 * (i16 & 3);
+  const float c = a.scale_log2;
+
+  f32x16 s[2];
+  T8 pf[4];
+
+  auto active = [&](int j) { return valid && (!CAUSAL || j * BC <= q0 + 31); };
+
+  // LDS operand reads are issued PF fragments ahead of the MFMA that consumes them, so that the
+  // matrix pipe does not idle on LDS latency.
+  constexpr int PF = 4;
+  auto k_frag = [&](const T* kbuf, int f) {  // f = 2 * kk + kb
+    return *(const T8*)(kbuf + (32 * (f & 1) + r) * KS + 16 * (f >> 1) + 8 * g);
+  };
+  auto v_frag = [&](const T* vbuf, int f) {  // f = DB * cc + db: consecutive MFMAs hit different accumulators
+    const T* vp = vbuf + v_lane_off + (16 * (f / DB)) * VS + 32 * (f % DB);
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vp));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vp + 8 * VS));
+    const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(T8, both);
+  };
+
+  // M block: O^T += V(jv)^T P^T (if do_pv) followed by S^T = K(js) Q^T (if do_s), as one
+  // software-pipelined stream of 4*DB + 2*KK MFMAs.
+  auto do_M = [&](bool do_pv, int jv, bool do_s, int js) {
+    const T* vbuf = Vs[jv & 1];
+    const T* kbuf = Ks[js & 1];
+    constexpr int NV = 4 * DB, NK = 2 * KK;
+    T8 ring[PF];
+    if (do_pv) {
+#pragma unroll
+      for (int f = 0; f < PF; ++f) ring[f] = v_frag(vbuf, f);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int f = 0; f < NV; ++f) {
+        const T8 cur = ring[f % PF];
+        o[f % DB] = mfma32(cur, pf[f / DB], o[f % DB]);
+        if (f + PF < NV) ring[f % PF] = v_frag(vbuf, f + PF);
+        else if (do_s) ring[f % PF] = k_frag(kbuf, f + PF - NV);
+        __builtin_amdgcn_sched_barrier(0);   // keep the prefetch distance the source states
+      }
+    } else if (do_s) {
+#pragma unroll
+      for (int f = 0; f < PF; ++f) ring[f] = k_frag(kbuf, f);
+    }
+    if (do_s) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s[kb][i] = 0.f;
+#pragma unroll
+      for (int f = 0; f < NK; ++f) {
+        // ring slot of K fragment f: it was loaded as "fragment NV + f" of the combined stream
+        const int slot = do_pv ? (NV + f) % PF : f % PF;
+        const T8 cur = ring[slot];
+        s[f & 1] = mfma32(cur, qf[f >> 1], s[f & 1]);
+        if (f + PF < NK) ring[slot] = k_frag(kbuf, f + PF);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+  };
+
+  auto do_softmax = [&](int j) {
+    const int k0 = j * BC;
+    if (CAUSAL && k0 + BC - 1 > q0) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int key = k0 + 32 * kb + 8 * (i >> 2) + 4 * g + (i & 3);
+          if (key > qi) s[kb][i] = -INFINITY;
+        }
+    }
+    float mx = s[0][0];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[kb][i]);
+    mx = fmaxf(mx, xchg32(mx)) * c;
+    // rescale only when some row of this wavefront saw a new maximum (wavefront-uniform branch)
+    if (__builtin_amdgcn_ballot_w64(mx > m_run) != 0) {
+      const float m_new = fmaxf(m_run, mx);
+      const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
+      m_run = m_new;
+      l_run *= alpha;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
+    }
+    const float m_use = (m_run == -INFINITY) ? 0.f : m_run;
+    float psum = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][i], c, -m_use));
+        s[kb][i] = p;
+        psum += p;
+      }
+    l_run += psum;
+    if constexpr (DROPOUT) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+          const uint32_t jg = (uint32_t)(k0 + 32 * kb + 8 * i4 + 4 * g) >> 2;
+          const u32x4 w = philox4x32_10(jg, (uint32_t)qi, (uint32_t)bh, a.offset_lo, a.seed_lo, a.seed_hi);
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (w[e] < a.drop_thr) s[kb][4 * i4 + e] = 0.f;
+        }
+    }
+#pragma unroll
+    for (int cc = 0; cc < 4; ++cc)
+#pragma unroll
+      for (int t = 0; t < 8; ++t) pf[cc][t] = (T)s[cc >> 1][8 * (cc & 1) + t];
+  };
+
+  // ---- prologue: K(0) into LDS; K(1), V(0) into registers (J >= 2 always)
+  gload_k(0);
+  sstore_k(0);
+  gload_k(1);
+  gload_v(0);
+  __syncthreads();
+  if (group_b) { __builtin_amdgcn_sched_barrier(0); __syncthreads(); }   // B runs one block behind A
+
+  for (int j = 0; j < J; ++j) {
+    // ---- M(j): publish this wavefront's share of K(j+1) and V(j), fetch the next tiles, matrix work
+    if (j + 1 < J) sstore_k((j + 1) & 1);
+    sstore_v(j & 1);
+    if (j + 2 < J) gload_k(j + 2);
+    if (j + 1 < J) gload_v(j + 1);
+    do_M(j > 0 && active(j - 1), j - 1, active(j), j);
+    __builtin_amdgcn_sched_barrier(0);
+    __syncthreads();
+    __builtin_amdgcn_sched_barrier(0);
+    // ---- X(j): online softmax
+    if (active(j)) do_softmax(j);
+    __builtin_amdgcn_sched_barrier(0);
+    __syncthreads();
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  do_M(active(J - 1), J - 1, false, 0);
+  if (!group_b) { __builtin_amdgcn_sched_barrier(0); __syncthreads(); }  // equal barrier counts
+
+  if (!valid) return;
+  const float l_tot = l_run + xchg32(l_run);
+  const float inv = l_tot > 0.f ? (DROPOUT ? a.keep_scale : 1.f) / l_tot : 0.f;
+  if (g == 0) {
+    const float lse = l_tot > 0.f ? (m_run + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f : -INFINITY;
+    a.LSE[(int64_t)bh * a.N + qi] = lse;
+  }
+  if (a.o_fp32) {
+    float* Og = (float*)a.O + head_off + (int64_t)qi * a.sn;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        f32x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = o[db][4 * i4 + e] * inv;
+        *(f32x4*)(Og + 32 * db + 8 * i4 + 4 * g) = v;
+      }
+  } else {
+    T* Og = (T*)a.O + head_off + (int64_t)qi * a.sn;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        T4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = (T)(o[db][4 * i4 + e] * inv);
+        *(T4*)(Og + 32 * db + 8 * i4 + 4 * g) = v;
+      }
+  }
+}
+
+template <typename T, int D>
+int launch_td(KArgs a, bool causal, bool dropout, hipStream_t s) {
+  const int n_qt = (a.N + BRW - 1) / BRW;
+  a.n_items = a.B * a.H * n_qt;
+  a.chunk = (a.n_items + kXcds - 1) / kXcds;
+  const dim3 grid(kXcds * a.chunk), block(NT);
+  if (!causal && !dropout) hipLaunchKernelGGL((fwd_pp_kernel<T, D, false, false>), grid, block, 0, s, a);
+  else if (causal && !dropout) hipLaunchKernelGGL((fwd_pp_kernel<T, D, true, false>), grid, block, 0, s, a);
+  else if (!causal && dropout) hipLaunchKernelGGL((fwd_pp_kernel<T, D, false, true>), grid, block, 0, s, a);
+  else hipLaunchKernelGGL((fwd_pp_kernel<T, D, true, true>), grid, block, 0, s, a);
+  return (int)hipGetLastError();
+}
+
+}  // namespace
+
+int launch_fwd_pp(const KArgs& a, int dtype, int d, bool causal, bool dropout, hipStream_t s) {
+  if (dtype == 0 && d == 64) return launch_td<_Float16, 64>(a, causal, dropout, s);
+  if (dtype == 0 && d == 128) return launch_td<_Float16, 128>(a, causal, dropout, s);
+  if (dtype == 1 && d == 64) return launch_td<__bf16, 64>(a, causal, dropout, s);
+  if (dtype == 1 && d == 128) return launch_td<__bf16, 128>(a, causal, dropout, s);
+  return (int)hipErrorInvalidValue;
+}
+
+}  // namespace attn
