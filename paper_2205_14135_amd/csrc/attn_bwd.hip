@@ -15,6 +15,9 @@
 // S and dP are therefore recomputed in both 2 and 3 (seven tile products per (i, j) instead of
 // five) in exchange for no atomics, no fp32 dQ round trip and bit-reproducible gradients.
 #include "attn_common.h"
+#include "attn_tiles.h"
+
+#include <cstdlib>
 
 namespace attn {
 namespace {
@@ -51,66 +54,6 @@ __global__ __launch_bounds__(256) void rowdot_kernel(const KArgs a) {
 #pragma unroll
   for (int s = CPR / 2; s >= 1; s >>= 1) acc += __shfl_xor(acc, s);
   if (row < rows && ch == 0) a.Dvec[row] = acc;
-}
-
-// Stages a [64][D] tile: global -> registers -> swizzled LDS.
-template <typename T, int D> struct TileStage {
-  typedef typename Vec<T>::x8 T8;
-  static constexpr int CPR = D / 8, RPP = NT / CPR, NP = TILE / RPP;
-  T8 reg[NP];
-  __device__ __forceinline__ void load(const T* g, int64_t sn, int row0) {
-    const int lrow = threadIdx.x / CPR, lchunk = threadIdx.x % CPR;
-#pragma unroll
-    for (int p = 0; p < NP; ++p)
-      reg[p] = *(const T8*)(g + (int64_t)(row0 + p * RPP + lrow) * sn + 8 * lchunk);
-  }
-  __device__ __forceinline__ void store(T* lds) const {
-    const int lrow = threadIdx.x / CPR, lchunk = threadIdx.x % CPR;
-#pragma unroll
-    for (int p = 0; p < NP; ++p) *(T8*)(lds + lds_off<D>(p * RPP + lrow, lchunk)) = reg[p];
-  }
-};
-
-// Per-lane LDS offsets for the transposing read of a swizzled tile (see attn_fwd.hip for the
-// access pattern): off[db][hi] addresses rows 4g + t (+8 if hi) of a 16-row chunk, d block db.
-template <int D> struct TrOffsets {
-  int off[D / 32][2];
-  __device__ __forceinline__ void init() {
-    const int lane = threadIdx.x & 63;
-    const int g = lane >> 5, i16 = lane & 15, q16 = lane >> 4;
-#pragma unroll
-    for (int hi = 0; hi < 2; ++hi) {
-      const int row = 4 * g + (i16 >> 2) + 8 * hi;
-#pragma unroll
-      for (int db = 0; db < D / 32; ++db) {
-        const int chunk = 4 * db + 2 * (q16 & 1) + ((i16 & 3) >> 1);
-        off[db][hi] = lds_off<D>(row, chunk) + 4 * (i16 & 1);
-      }
-    }
-  }
-};
-
-template <typename T8>
-__device__ __forceinline__ T8 tr_frag(const void* lds_lo, const void* lds_hi) {
-  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(lds_lo));
-  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(lds_hi));
-  const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-  return __builtin_bit_cast(T8, both);
-}
-
-// Writes a transposed accumulator (rows = d, column = this lane's token) as a token row.
-template <typename T, int D>
-__device__ __forceinline__ void store_rows(T* dst_row, const f32x16 (&acc)[D / 32], float scale, int g) {
-  typedef typename Vec<T>::x4 T4;
-#pragma unroll
-  for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-    for (int i4 = 0; i4 < 4; ++i4) {
-      T4 v;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) v[e] = (T)(acc[db][4 * i4 + e] * scale);
-      *(T4*)(dst_row + 32 * db + 8 * i4 + 4 * g) = v;
-    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -164,7 +107,7 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const KArgs a) {
   }
   TrOffsets<D> tro;
   tro.init();
-  TileStage<T, D> ks, vs;
+  TileStage<T, D, NT> ks, vs;
 
   const float c = a.scale_log2;
   int jt = it.next();
@@ -279,7 +222,7 @@ __global__ __launch_bounds__(NT, 1) void dkv_kernel(const KArgs a) {
     it.init(nullptr, 0, CAUSAL ? 2 * kt : 0, a.N / TILE);
   TrOffsets<D> tro;
   tro.init();
-  TileStage<T, D> qs, gs;
+  TileStage<T, D, NT> qs, gs;
   float lreg = 0.f, dreg = 0.f;
   auto load_stats = [&](int row0) {
     if (threadIdx.x < TILE) {
@@ -383,6 +326,9 @@ __global__ __launch_bounds__(NT, 1) void dkv_kernel(const KArgs a) {
   store_rows<T, D>((T*)a.dK + head_off + (int64_t)kj * a.sn, dk, a.tau, g);
 }
 
+template <typename T> constexpr int kDtype = 0;
+template <> constexpr int kDtype<__bf16> = 1;
+
 template <typename T, int D>
 int launch_bwd_td(const KArgs& a, bool causal, bool dropout, bool sparse, hipStream_t s, hipEvent_t* ev) {
   const int64_t rows = (int64_t)a.B * a.H * a.N;
@@ -393,14 +339,23 @@ int launch_bwd_td(const KArgs& a, bool causal, bool dropout, bool sparse, hipStr
   if (e != 0) return e;
   if (ev) (void)hipEventRecord(ev[1], s);
   const dim3 grid(kXcds * a.chunk), block(NT);
+  // ATTN_DKV_VARIANT=base selects the single-role dK/dV kernel of this file (bench-time comparison)
+  static const bool dkv_base = [] {
+    const char* v = getenv("ATTN_DKV_VARIANT");
+    return v != nullptr && v[0] == 'b';
+  }();
 #define ATTN_BWD_CASE(C, P, S)                                                   \
   if (causal == C && dropout == P && sparse == S) {                              \
     hipLaunchKernelGGL((dq_kernel<T, D, C, P, S>), grid, block, 0, s, a);        \
     e = (int)hipGetLastError();                                                  \
     if (e != 0) return e;                                                        \
     if (ev) (void)hipEventRecord(ev[2], s);                                      \
-    hipLaunchKernelGGL((dkv_kernel<T, D, C, P, S>), grid, block, 0, s, a);       \
-    e = (int)hipGetLastError();                                                  \
+    if (dkv_base) {                                                              \
+      hipLaunchKernelGGL((dkv_kernel<T, D, C, P, S>), grid, block, 0, s, a);     \
+      e = (int)hipGetLastError();                                                \
+    } else {                                                                     \
+      e = launch_dkv_rs(a, kDtype<T>, D, C, P, S, s);                            \
+    }                                                                            \
     if (ev) (void)hipEventRecord(ev[3], s);                                      \
     return e;                                                                    \
   }

@@ -1,0 +1,263 @@
+// dK / dV kernel of the backward pass with the work of a key block split by ROLE between two
+// wavefronts that share a SIMD.
+//
+// Arithmetic: Algorithm 4 of the paper for one block of 128 keys, swept over 64-query tiles:
+//     S = Q K^T, P = exp(S - L), dV += (P o Z)^T dO, dP = (dO V^T) o Z, dS = P o (dP - D), dK += tau dS^T Q.
+// A workgroup is 8 wavefronts.  Wavefronts w and w + 4 (same SIMD) both own keys
+// kt*128 + 32 w .. + 31, in the "lane = key" register layout (see attn_bwd.hip), but
+//     role A (w < 4):  S tile -> P (exp) -> dV^T += dO^T P_dropped      keeps K fragments, dV accumulator
+//     role B (w >= 4): dP tile -> dS = P (dP Z - D) -> dK^T += Q^T dS   keeps V fragments, dK accumulator
+// so each wavefront needs half of the accumulators and operand fragments (<= 256 registers, two
+// wavefronts per SIMD), the four tile products are done once each, and the two different
+// instruction streams on a SIMD overlap MFMA with the exp / dS VALU work.  B needs A's P: A
+// leaves it (16-bit, in B's own register layout, plus the dropout keep bits) in LDS, and B runs
+// its dS / dK part one tile behind, so one workgroup barrier per tile orders everything.
+// LDS: Q tiles x3 (Q(j) is read by A in iteration j and by B in iteration j+1), dO tiles x2,
+// row statistics, P exchange x2.
+#include "attn_common.h"
+#include "attn_tiles.h"
+
+namespace attn {
+namespace {
+
+constexpr int NT = 512;
+constexpr int TILE = 64;
+
+template <typename T, int D, bool CAUSAL, bool DROPOUT, bool SPARSE>
+__global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
+  typedef typename Vec<T>::x8 T8;
+  constexpr int KK = D / 16, DB = D / 32;
+  __shared__ __attribute__((aligned(16))) T Qs[3][TILE * D];
+  __shared__ __attribute__((aligned(16))) T Gs[2][TILE * D];      // dO tiles
+  __shared__ __attribute__((aligned(16))) float Ls[2][TILE];      // base-2 row statistic
+  __shared__ __attribute__((aligned(16))) float Ds[3][TILE];      // D_i
+  __shared__ __attribute__((aligned(16))) T8 Px[2][4][4][64];     // P exchange [buf][pair][chunk][lane]
+  __shared__ uint32_t Kw[2][4][64];                                // dropout keep words [buf][pair][lane]
+
+  const int item = xcd_item(a.n_items, a.chunk);
+  if (item < 0) return;
+  const int n_kt = a.N / 128;
+  const int bh = item / n_kt;
+  const int kt = item % n_kt;
+  const int b = bh / a.H, h = bh % a.H;
+  const int64_t head_off = (int64_t)b * a.sb + (int64_t)h * a.sh;
+  const T* __restrict__ Qg = (const T*)a.Q + head_off;
+  const T* __restrict__ Gg = (const T*)a.dO + head_off;
+  const float* __restrict__ Lg = a.LSE + (int64_t)bh * a.N;
+  const float* __restrict__ Dg = a.Dvec + (int64_t)bh * a.N;
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const bool role_b = wave >= 4;
+  const int pair = wave & 3;
+  const int r = lane & 31, g = lane >> 5;
+  const int kw0 = kt * 128 + pair * 32;
+  const int kj = kw0 + r;  // this lane's key
+
+  // loop-invariant B operands: K fragments for role A, V fragments for role B
+  T8 kvf[KK];
+  {
+    const T* src = role_b ? (const T*)a.V : (const T*)a.K;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk)
+      kvf[kk] = *(const T8*)(src + head_off + (int64_t)kj * a.sn + 16 * kk + 8 * g);
+  }
+  f32x16 acc[DB];  // role A: dV^T, role B: dK^T   (rows d, column = this lane's key)
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[db][i] = 0.f;
+  f32x16 sd[2];    // role A: S, role B: dP   (rows = queries of the tile, column = key)
+
+  TileIter<SPARSE> it;
+  if constexpr (SPARSE)
+    it.init(a.mask + (int64_t)h * a.mask_sh + kt, a.T, CAUSAL ? kt : 0, a.T);
+  else
+    it.init(nullptr, 0, CAUSAL ? 2 * kt : 0, a.N / TILE);
+  TrOffsets<D> tro;
+  tro.init();
+  TileStage<T, D, NT> qs, gs;
+  float lreg = 0.f, dreg = 0.f;
+  auto load_tile = [&](int t) {
+    qs.load(Qg, a.sn, t * TILE);
+    gs.load(Gg, a.sn, t * TILE);
+    if (threadIdx.x < TILE) {
+      const float lse = Lg[t * TILE + threadIdx.x];
+      lreg = (lse == -INFINITY) ? INFINITY : lse * 1.4426950408889634f;
+      dreg = Dg[t * TILE + threadIdx.x];
+    }
+  };
+  auto store_tile = [&](int q3, int p2) {
+    qs.store(Qs[q3]);
+    gs.store(Gs[p2]);
+    if (threadIdx.x < TILE) { Ls[p2][threadIdx.x] = lreg; Ds[q3][threadIdx.x] = dreg; }
+  };
+
+  const float c = a.scale_log2;
+
+  // product of a row-read tile with the register fragments: sd[qb] = Tile[32 qb .. +31][:] . kvf
+  auto row_product = [&](const T* tile) {
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) sd[qb][i] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk)
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb)
+        sd[qb] = mfma32(*(const T8*)(tile + lds_off<D>(32 * qb + r, 2 * kk + g)), kvf[kk], sd[qb]);
+  };
+  // acc^T += Tile^T . frag   (contraction over the 64 queries of the tile)
+  auto col_product = [&](const T* tile, const T8 (&frag)[4]) {
+#pragma unroll
+    for (int cc = 0; cc < 4; ++cc)
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        const T* base = tile + 16 * cc * D;
+        acc[db] = mfma32(tr_frag<T8>(base + tro.off[db][0], base + tro.off[db][1]), frag[cc], acc[db]);
+      }
+  };
+  auto keep_from_word = [&](uint32_t mine, uint32_t (&keep_from)[4]) {
+    // bits drawn by the quad lane that handled query e, shifted so that bit 4n is this lane's key
+    keep_from[0] = (uint32_t)__builtin_amdgcn_mov_dpp((int)mine, 0x00, 0xF, 0xF, true) >> (r & 3);
+    keep_from[1] = (uint32_t)__builtin_amdgcn_mov_dpp((int)mine, 0x55, 0xF, 0xF, true) >> (r & 3);
+    keep_from[2] = (uint32_t)__builtin_amdgcn_mov_dpp((int)mine, 0xAA, 0xF, 0xF, true) >> (r & 3);
+    keep_from[3] = (uint32_t)__builtin_amdgcn_mov_dpp((int)mine, 0xFF, 0xF, 0xF, true) >> (r & 3);
+  };
+
+  // ---- role A, tile with first query i0, buffers (q3, p2)
+  auto role_a = [&](int i0, int q3, int p2) {
+    row_product(Qs[q3]);                                   // S = Q K^T
+    uint32_t keep_from[4] = {0, 0, 0, 0};
+    if constexpr (DROPOUT) {
+      // a lane draws for query (r % 4) of each group of four consecutive queries; the four
+      // lanes of a quad (four consecutive keys) exchange the results
+      uint32_t mine = 0;
+#pragma unroll
+      for (int n = 0; n < 8; ++n) {  // n = 4 qb + i4
+        const uint32_t qrow = (uint32_t)(i0 + 32 * (n >> 2) + 8 * (n & 3) + 4 * g + (r & 3));
+        const u32x4 w = philox4x32_10((uint32_t)kj >> 2, qrow, (uint32_t)bh, a.offset_lo, a.seed_lo, a.seed_hi);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) mine |= (w[e] >= a.drop_thr ? 1u : 0u) << (4 * n + e);
+      }
+      Kw[p2][pair][lane] = mine;
+      keep_from_word(mine, keep_from);
+    }
+    T8 pf[4], pfull[4];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        const f32x4 l4 = *(const f32x4*)(&Ls[p2][32 * qb + 8 * i4 + 4 * g]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int i = 4 * i4 + e;
+          float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sd[qb][i], c, -l4[e]));
+          if (CAUSAL && kj > i0 + 32 * qb + 8 * i4 + 4 * g + e) p = 0.f;
+          const int cc = 2 * qb + (i4 >> 1), t = 4 * (i4 & 1) + e;
+          pfull[cc][t] = (T)p;
+          if constexpr (DROPOUT) {
+            const bool keep = (keep_from[e] >> (4 * (4 * qb + i4))) & 1u;
+            pf[cc][t] = (T)(keep ? p : 0.f);
+          }
+        }
+      }
+#pragma unroll
+    for (int cc = 0; cc < 4; ++cc) Px[p2][pair][cc][lane] = pfull[cc];
+    if constexpr (DROPOUT) col_product(Gs[p2], pf);        // dV^T += dO^T P_dropped
+    else col_product(Gs[p2], pfull);
+  };
+  // ---- role B, second half for the previous tile: dS from sd (= dP) and A's P, then dK
+  auto role_b_ds_dk = [&](int q3, int p2) {
+    uint32_t keep_from[4] = {0, 0, 0, 0};
+    if constexpr (DROPOUT) keep_from_word(Kw[p2][pair][lane], keep_from);
+    T8 pin[4], dsf[4];
+#pragma unroll
+    for (int cc = 0; cc < 4; ++cc) pin[cc] = Px[p2][pair][cc][lane];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        const f32x4 d4 = *(const f32x4*)(&Ds[q3][32 * qb + 8 * i4 + 4 * g]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int i = 4 * i4 + e;
+          const int cc = 2 * qb + (i4 >> 1), t = 4 * (i4 & 1) + e;
+          float dpv = sd[qb][i];
+          if constexpr (DROPOUT) {
+            const bool keep = (keep_from[e] >> (4 * (4 * qb + i4))) & 1u;
+            dpv = keep ? dpv * a.keep_scale : 0.f;
+          }
+          dsf[cc][t] = (T)((float)pin[cc][t] * (dpv - d4[e]));
+        }
+      }
+    col_product(Qs[q3], dsf);                               // dK^T += Q^T dS
+  };
+
+  // ---- pipeline over the tiles of this key block
+  int t0 = it.next();
+  int t1 = t0 >= 0 ? it.next() : -1;
+  if (t0 >= 0) { load_tile(t0); store_tile(0, 0); }
+  if (t1 >= 0) load_tile(t1);
+  int q3 = 0, p2 = 0;          // buffer indices of the current tile: j % 3 and j % 2
+  bool have_prev = false, prev_active = false;
+  while (t0 >= 0) {
+    __syncthreads();
+    const int t2 = t1 >= 0 ? it.next() : -1;
+    const int q3n = q3 == 2 ? 0 : q3 + 1;
+    if (t1 >= 0) {
+      store_tile(q3n, p2 ^ 1);
+      if (t2 >= 0) load_tile(t2);
+    }
+    const int i0 = t0 * TILE;
+    const bool active = !CAUSAL || i0 + TILE - 1 >= kw0;
+    if (!role_b) {
+      if (active) role_a(i0, q3, p2);
+    } else {
+      if (have_prev && prev_active) role_b_ds_dk(q3 == 0 ? 2 : q3 - 1, p2 ^ 1);
+      if (active) row_product(Gs[p2]);                     // dP = dO V^T
+    }
+    have_prev = true;
+    prev_active = active;
+    t0 = t1;
+    t1 = t2;
+    q3 = q3n;
+    p2 ^= 1;
+  }
+  __syncthreads();
+  if (role_b && have_prev && prev_active) role_b_ds_dk(q3 == 0 ? 2 : q3 - 1, p2 ^ 1);
+
+  if (!role_b) store_rows<T, D>((T*)a.dV + head_off + (int64_t)kj * a.sn, acc, DROPOUT ? a.keep_scale : 1.f, g);
+  else store_rows<T, D>((T*)a.dK + head_off + (int64_t)kj * a.sn, acc, a.tau, g);
+}
+
+template <typename T, int D>
+int launch_td(const KArgs& a, bool causal, bool dropout, bool sparse, hipStream_t s) {
+  const dim3 grid(kXcds * a.chunk), block(NT);
+#define ATTN_DKV_CASE(C, P, S)                                                    \
+  if (causal == C && dropout == P && sparse == S) {                               \
+    hipLaunchKernelGGL((dkv_rs_kernel<T, D, C, P, S>), grid, block, 0, s, a);     \
+    return (int)hipGetLastError();                                                \
+  }
+  ATTN_DKV_CASE(false, false, false)
+  ATTN_DKV_CASE(true, false, false)
+  ATTN_DKV_CASE(false, true, false)
+  ATTN_DKV_CASE(true, true, false)
+  ATTN_DKV_CASE(false, false, true)
+  ATTN_DKV_CASE(true, false, true)
+  ATTN_DKV_CASE(false, true, true)
+  ATTN_DKV_CASE(true, true, true)
+#undef ATTN_DKV_CASE
+  return (int)hipErrorInvalidValue;
+}
+
+}  // namespace
+
+int launch_dkv_rs(const KArgs& a, int dtype, int d, bool causal, bool dropout, bool sparse, hipStream_t s) {
+  if (dtype == 0 && d == 64) return launch_td<_Float16, 64>(a, causal, dropout, sparse, s);
+  if (dtype == 0 && d == 128) return launch_td<_Float16, 128>(a, causal, dropout, sparse, s);
+  if (dtype == 1 && d == 64) return launch_td<__bf16, 64>(a, causal, dropout, sparse, s);
+  if (dtype == 1 && d == 128) return launch_td<__bf16, 128>(a, causal, dropout, sparse, s);
+  return (int)hipErrorInvalidValue;
+}
+
+}  // namespace attn
