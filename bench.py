@@ -145,14 +145,24 @@ def run_gpu(cfg, steps, warmup, seed):
         bwd(e[1:5])
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
-    names = ["fwd_kernel", "rowdot_kernel", "dq_kernel", "dkv_kernel"]
+    # event intervals, labelled with the kernels the library launches for this workload (the forward
+    # choice mirrors launch_fwd() in csrc/attn_fwd.hip)
+    if cfg["sparse"]:
+        use_pp = False
+    elif cfg["p"] > 0:
+        use_pp = d == 128
+    elif d == 128:
+        use_pp = N >= (4096 if cfg["causal"] else 512)
+    else:
+        use_pp = N >= (8192 if cfg["causal"] else 2048)
+    names = ["fwd_pp_kernel" if use_pp else "fwd_kernel", "rowdot_kernel", "dq_kernel", "dkv_rs_kernel"]
     dur = {n: 0.0 for n in names}
     for e in evs:
         for i, n in enumerate(names):
             dur[n] += hev.elapsed_ms(e[i], e[i + 1])
     dur = {n: v / steps for n, v in dur.items()}
     hev.close()
-    return dict(ms_per_step=wall_ms / steps, kernel_ms=dur, nnz=nnz, tensors=t, block_mask=bm_np, tau=tau)
+    return dict(ms_per_step=wall_ms / steps, kernel_ms=dur, names=names, nnz=nnz, tensors=t, block_mask=bm_np, tau=tau)
 
 
 def cpu_baseline(cfg, run, budget_s=12.0, max_s=30.0):
@@ -254,12 +264,12 @@ def main():
             c = wl[name]
             r = run_gpu(c, max(3, args.steps // 3), 2, inputs.BASE_SEED + 3)
             f = flops_fwd(c, r["nnz"])
-            k = r["kernel_ms"]
-            bwd_ms = k["rowdot_kernel"] + k["dq_kernel"] + k["dkv_kernel"]
-            print(json.dumps(dict(workload=name, fwd_ms=round(k["fwd_kernel"], 4), bwd_ms=round(bwd_ms, 4),
-                                  fwd_tflops=round(f / k["fwd_kernel"] * 1e-9, 1),
+            k = [r["kernel_ms"][n] for n in r["names"]]
+            fwd_ms, bwd_ms = k[0], k[1] + k[2] + k[3]
+            print(json.dumps(dict(workload=name, fwd_ms=round(fwd_ms, 4), bwd_ms=round(bwd_ms, 4),
+                                  fwd_tflops=round(f / fwd_ms * 1e-9, 1),
                                   bwd_tflops=round(2.5 * f / bwd_ms * 1e-9, 1),
-                                  fwd_bwd_tflops=round(3.5 * f / (k["fwd_kernel"] + bwd_ms) * 1e-9, 1))),
+                                  fwd_bwd_tflops=round(3.5 * f / (fwd_ms + bwd_ms) * 1e-9, 1))),
                   file=sys.stderr, flush=True)
 
     cfg = wl[args.workload]
@@ -270,7 +280,8 @@ def main():
     kms = run["kernel_ms"]
     # algorithmic FLOPs of each launch: forward two tile products; dK/dV kernel four of the five
     # backward products (S, dP, dV, dK); dQ kernel one (its S and dP are recomputation)
-    algo = {"fwd_kernel": f_fwd, "dq_kernel": 0.5 * f_fwd, "dkv_kernel": 2.0 * f_fwd}
+    n_fwd, _, n_dq, n_dkv = run["names"]
+    algo = {n_fwd: f_fwd, n_dq: 0.5 * f_fwd, n_dkv: 2.0 * f_fwd}
     dominant = max(algo, key=lambda n: kms[n])
     achieved = algo[dominant] / kms[dominant] * 1e-9
     peak = PEAK_TFLOPS[cfg["dtype"]]

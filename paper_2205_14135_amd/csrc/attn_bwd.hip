@@ -339,7 +339,8 @@ int launch_bwd_td(const KArgs& a, bool causal, bool dropout, bool sparse, hipStr
   if (e != 0) return e;
   if (ev) (void)hipEventRecord(ev[1], s);
   const dim3 grid(kXcds * a.chunk), block(NT);
-  // ATTN_DKV_VARIANT=base selects the single-role dK/dV kernel of this file (bench-time comparison)
+  // ATTN_DKV_VARIANT=base selects the single-role dK/dV kernel of this file instead of the
+  // role-split one (bench-time comparison)
   static const bool dkv_base = [] {
     const char* v = getenv("ATTN_DKV_VARIANT");
     return v != nullptr && v[0] == 'b';
