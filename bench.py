@@ -115,8 +115,9 @@ def run_gpu(cfg, steps, warmup, seed):
     O = torch.empty_like(g["Q"])
     L = torch.empty((B, H, N), dtype=torch.float32, device=dev)
     grads = tuple(torch.empty_like(g["Q"]) for _ in range(3))
-    ws = torch.empty(max(256, binding.attn_bwd_workspace_bytes(binding.make_params(g["Q"], tau))),
-                     dtype=torch.uint8, device=dev)
+    pp = binding.make_params(g["Q"], tau)
+    ws_bytes = binding.attn_blocksparse_bwd_workspace_bytes(pp) if cfg["sparse"] else binding.attn_bwd_workspace_bytes(pp)
+    ws = torch.empty(max(256, ws_bytes), dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream(dev).cuda_stream
     hev = HipEvents()
 

@@ -104,6 +104,14 @@ int attn_fwd(const attn_params* p, const void* Q, const void* K, const void* V,
 size_t attn_bwd_workspace_bytes(const attn_params* p);
 
 /*
+ * Same for attn_blocksparse_bwd (and attn_bwd_timed with a mask): additionally holds the
+ * per-column block counts and fp32 dK/dV accumulators used when a mask column keeps so many
+ * blocks (a "global token" column) that its work is split over several workgroups.  Still
+ * linear in B*H*N*d.  Returns 0 if the params are invalid.
+ */
+size_t attn_blocksparse_bwd_workspace_bytes(const attn_params* p);
+
+/*
  * Backward pass (Algorithm 4, with D_i = rowsum(dO_i o O_i) from Eq. (4) of
  * Appendix B.2).
  *   Q, K, V, O, dO : in,  [B,H,N,d] (O as written by attn_fwd with the same params)
@@ -133,7 +141,10 @@ int attn_blocksparse_fwd(const attn_params* p, const uint8_t* block_mask, int32_
 /*
  * Block-sparse backward: Algorithm 4 restricted to the non-zero blocks (the
  * paper states only that the backward skips the same blocks, Section 3.3).
- * Arguments as attn_bwd plus the mask arguments of attn_blocksparse_fwd.
+ * Arguments as attn_bwd plus the mask arguments of attn_blocksparse_fwd; the workspace must
+ * hold attn_blocksparse_bwd_workspace_bytes(p) bytes.  dK and dV of mask columns that are split
+ * over several workgroups are summed with fp32 atomics, so their last bits may differ from run
+ * to run; everything else is bit-reproducible.
  */
 int attn_blocksparse_bwd(const attn_params* p, const uint8_t* block_mask, int32_t mask_block,
                          int64_t mask_stride_h, const void* Q, const void* K, const void* V,

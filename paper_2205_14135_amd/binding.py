@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libattn_gfx950.so")
 ATTN_FP16, ATTN_BF16 = 0, 1
 
 SYMBOLS = (
-    "attn_fwd", "attn_bwd_workspace_bytes", "attn_bwd", "attn_blocksparse_fwd",
+    "attn_fwd", "attn_bwd_workspace_bytes", "attn_blocksparse_bwd_workspace_bytes", "attn_bwd", "attn_blocksparse_fwd",
     "attn_blocksparse_bwd", "attn_bwd_timed", "attn_debug_dropout_mask", "attn_strerror",
     "attn_version",
 )
@@ -63,6 +63,8 @@ def load() -> ctypes.CDLL:
     lib.attn_fwd.restype = ctypes.c_int
     lib.attn_bwd_workspace_bytes.argtypes = [P]
     lib.attn_bwd_workspace_bytes.restype = sz
+    lib.attn_blocksparse_bwd_workspace_bytes.argtypes = [P]
+    lib.attn_blocksparse_bwd_workspace_bytes.restype = sz
     lib.attn_bwd.argtypes = [P] + [vp] * 9 + [vp, sz]
     lib.attn_bwd.restype = ctypes.c_int
     lib.attn_blocksparse_fwd.argtypes = [P, vp, i32, i64, vp, vp, vp, vp, vp]
@@ -163,8 +165,12 @@ def attn_bwd_workspace_bytes(p: AttnParams) -> int:
     return int(load().attn_bwd_workspace_bytes(ctypes.byref(p)))
 
 
-def _workspace(p: AttnParams, device, workspace):
-    need = attn_bwd_workspace_bytes(p)
+def attn_blocksparse_bwd_workspace_bytes(p: AttnParams) -> int:
+    return int(load().attn_blocksparse_bwd_workspace_bytes(ctypes.byref(p)))
+
+
+def _workspace(p: AttnParams, device, workspace, sparse=False):
+    need = attn_blocksparse_bwd_workspace_bytes(p) if sparse else attn_bwd_workspace_bytes(p)
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=device)
     return workspace, workspace.numel() * workspace.element_size()
@@ -212,7 +218,7 @@ def attn_blocksparse_bwd(Q, K, V, O, dO, LSE, block_mask, *, softmax_scale, mask
         grads = tuple(torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device)
                       for _ in range(3))
     dQ, dK, dV = grads
-    workspace, nbytes = _workspace(p, Q.device, workspace)
+    workspace, nbytes = _workspace(p, Q.device, workspace, sparse=True)
     _check(load().attn_blocksparse_bwd(ctypes.byref(p), _ptr(block_mask), int(mask_block), int(msh),
                                        _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE),
                                        _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(workspace), nbytes),
@@ -232,7 +238,7 @@ def attn_bwd_timed(Q, K, V, O, dO, LSE, events, *, softmax_scale, block_mask=Non
         grads = tuple(torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device)
                       for _ in range(3))
     dQ, dK, dV = grads
-    workspace, nbytes = _workspace(p, Q.device, workspace)
+    workspace, nbytes = _workspace(p, Q.device, workspace, sparse=block_mask is not None)
     ev = (ctypes.c_void_p * 4)(*[ctypes.c_void_p(int(e)) for e in events])
     _check(load().attn_bwd_timed(ctypes.byref(p), _ptr(block_mask), int(mask_block), int(msh),
                                  _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE),

@@ -73,6 +73,17 @@ void set_items(attn::KArgs& k, int tiles_per_head) {
   k.chunk = (k.n_items + attn::kXcds - 1) / attn::kXcds;
 }
 
+// Backward scratch layout: D vector | (block-sparse only) column counts | fp32 dK | fp32 dV.
+struct WsLayout { size_t d_bytes, cnt_bytes, acc_bytes; };
+WsLayout ws_layout(const attn_params* p) {
+  WsLayout w;
+  w.d_bytes = align_up((size_t)p->B * p->H * p->N * sizeof(float), 256);
+  // column counts, then the segment list: one counter plus at most kMaxSegs entries per column
+  w.cnt_bytes = align_up(((size_t)p->B * p->H * (p->N / attn::kMaskBlock) * (1 + attn::kMaxSegs) + 64) * sizeof(int), 256);
+  w.acc_bytes = align_up((size_t)p->B * p->H * p->N * p->d * sizeof(float), 256);
+  return w;
+}
+
 int fwd_common(const attn_params* p, const uint8_t* mask, int64_t mask_sh, bool sparse,
                const void* Q, const void* K, const void* V, void* O, float* LSE) {
   Checked c;
@@ -94,11 +105,18 @@ int bwd_common(const attn_params* p, const uint8_t* mask, int64_t mask_sh, bool 
   const int st = check_params(p, &c);
   if (st != ATTN_OK) return st;
   if (!Q || !K || !V || !O || !dO || !LSE || !dQ || !dK || !dV) return ATTN_ERR_NULL;
-  const size_t need = attn_bwd_workspace_bytes(p);
+  const size_t need = sparse ? attn_blocksparse_bwd_workspace_bytes(p) : attn_bwd_workspace_bytes(p);
   if (ws == nullptr || ((uintptr_t)ws & 255u) != 0 || ws_bytes < need) return ATTN_ERR_WORKSPACE;
   c.k.Q = Q; c.k.K = K; c.k.V = V; c.k.O = const_cast<void*>(O); c.k.LSE = const_cast<float*>(LSE);
   c.k.dO = dO; c.k.dQ = dQ; c.k.dK = dK; c.k.dV = dV;
   c.k.Dvec = (float*)ws;
+  if (sparse) {
+    const WsLayout w = ws_layout(p);
+    c.k.seglist = (int*)((char*)ws + w.d_bytes);
+    c.k.colcnt = c.k.seglist + 64 + (size_t)p->B * p->H * (p->N / attn::kMaskBlock) * attn::kMaxSegs;
+    c.k.dKacc = (float*)((char*)ws + w.d_bytes + w.cnt_bytes);
+    c.k.dVacc = (float*)((char*)ws + w.d_bytes + w.cnt_bytes + w.acc_bytes);
+  }
   c.k.mask = mask; c.k.mask_sh = mask_sh;
   set_items(c.k, c.k.N / 128);
   hipEvent_t ev[4];
@@ -126,6 +144,13 @@ size_t attn_bwd_workspace_bytes(const attn_params* p) {
   if (check_params(p, &c) != ATTN_OK) return 0;
   // D_i = rowsum(dO_i o O_i): one float per row
   return align_up((size_t)p->B * p->H * p->N * sizeof(float), 256);
+}
+
+size_t attn_blocksparse_bwd_workspace_bytes(const attn_params* p) {
+  Checked c;
+  if (check_params(p, &c) != ATTN_OK) return 0;
+  const WsLayout w = ws_layout(p);
+  return w.d_bytes + w.cnt_bytes + 2 * w.acc_bytes;
 }
 
 int attn_bwd(const attn_params* p, const void* Q, const void* K, const void* V, const void* O,

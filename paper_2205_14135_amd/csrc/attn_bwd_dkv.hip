@@ -22,6 +22,7 @@ namespace {
 
 constexpr int NT = 512;
 constexpr int TILE = 64;
+constexpr int kListGroups = 512;
 
 template <typename T, int D, bool CAUSAL, bool DROPOUT, bool SPARSE>
 __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
@@ -34,9 +35,35 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
   __shared__ __attribute__((aligned(16))) T8 Px[2][4][4][64];     // P exchange [buf][pair][chunk][lane]
   __shared__ uint32_t Kw[2][4][64];                                // dropout keep words [buf][pair][lane]
 
-  const int item = xcd_item(a.n_items, a.chunk);
-  if (item < 0) return;
   const int n_kt = a.N / 128;
+  // Work assignment.  Dense: one key block per workgroup.  Block-sparse: the first 8 * chunk
+  // workgroups take one mask column each and leave the heavy ones (many kept blocks, e.g. a
+  // global-token column) alone; those were cut into segments by sparse_prep_kernel and the
+  // remaining workgroups walk that segment list.
+  const int n_col_groups = kXcds * a.chunk;
+  const bool list_mode = SPARSE && (int)blockIdx.x >= n_col_groups;
+  for (int round = 0;; ++round) {
+  int item, skip_blocks = 0, take_blocks = 0x7fffffff;
+  bool heavy = false;
+  if (!list_mode) {
+    item = xcd_item(a.n_items, a.chunk);
+    if (item < 0) return;
+    if constexpr (SPARSE) {
+      if (a.colcnt[item] > kHeavyBlocks) return;
+    }
+  } else {
+    const int idx = ((int)blockIdx.x - n_col_groups) + round * ((int)gridDim.x - n_col_groups);
+    if (idx >= a.seglist[0]) return;
+    const int e = a.seglist[1 + idx];
+    item = e / kMaxSegs;
+    const int seg = e % kMaxSegs;
+    const int cnt = a.colcnt[item];
+    const int nseg = min((int)kMaxSegs, (cnt + kSegBlocks - 1) / kSegBlocks);
+    const int len = (cnt + nseg - 1) / nseg;
+    skip_blocks = seg * len;
+    take_blocks = len;
+    heavy = true;
+  }
   const int bh = item / n_kt;
   const int kt = item % n_kt;
   const int b = bh / a.H, h = bh % a.H;
@@ -70,7 +97,7 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
 
   TileIter<SPARSE> it;
   if constexpr (SPARSE)
-    it.init(a.mask + (int64_t)h * a.mask_sh + kt, a.T, CAUSAL ? kt : 0, a.T);
+    it.init(a.mask + (int64_t)h * a.mask_sh + kt, a.T, CAUSAL ? kt : 0, a.T, skip_blocks, take_blocks);
   else
     it.init(nullptr, 0, CAUSAL ? 2 * kt : 0, a.N / TILE);
   TrOffsets<D> tro;
@@ -226,17 +253,97 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
   __syncthreads();
   if (role_b && have_prev && prev_active) role_b_ds_dk(q3 == 0 ? 2 : q3 - 1, p2 ^ 1);
 
-  if (!role_b) store_rows<T, D>((T*)a.dV + head_off + (int64_t)kj * a.sn, acc, DROPOUT ? a.keep_scale : 1.f, g);
-  else store_rows<T, D>((T*)a.dK + head_off + (int64_t)kj * a.sn, acc, a.tau, g);
+  const float out_scale = role_b ? a.tau : (DROPOUT ? a.keep_scale : 1.f);
+  if (SPARSE && heavy) {
+    // one of several segments of this column: sum in fp32; sparse_finish_kernel converts
+    float* dst = (role_b ? a.dKacc : a.dVacc) + ((int64_t)bh * a.N + kj) * D;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int i = 0; i < 16; ++i)
+        unsafeAtomicAdd(dst + 32 * db + 8 * (i >> 2) + 4 * g + (i & 3), acc[db][i] * out_scale);
+  } else {
+    store_rows<T, D>((T*)(role_b ? a.dK : a.dV) + head_off + (int64_t)kj * a.sn, acc, out_scale, g);
+  }
+  if (!list_mode) return;
+  __syncthreads();   // LDS is reused by the next segment
+  }  // for round
+}
+
+// Block-sparse preparation: kept blocks per mask column (rows >= column under a causal mask),
+// and zeroed fp32 accumulators for the columns that will be split.  One 64-thread group per (bh, kt).
+template <int D>
+__global__ __launch_bounds__(64) void sparse_prep_kernel(const KArgs a) {
+  const int item = blockIdx.x;
+  const int n_kt = a.T;
+  const int bh = item / n_kt, kt = item % n_kt;
+  const int h = bh % a.H;
+  const uint8_t* col = a.mask + (int64_t)h * a.mask_sh + kt;
+  int cnt = 0;
+  for (int base = a.causal ? kt : 0; base < a.T; base += 64) {
+    const int blk = base + (int)threadIdx.x;
+    const bool on = blk < a.T && blk >= (a.causal ? kt : 0) && col[(int64_t)blk * a.T] != 0;
+    cnt += __builtin_popcountll(__ballot(on));
+  }
+  if (threadIdx.x == 0) a.colcnt[item] = cnt;
+  if (cnt > kHeavyBlocks) {
+    if (threadIdx.x == 0) {
+      const int nseg = min((int)kMaxSegs, (cnt + kSegBlocks - 1) / kSegBlocks);
+      const int at = atomicAdd(a.seglist, nseg);
+      for (int sgi = 0; sgi < nseg; ++sgi) a.seglist[1 + at + sgi] = item * kMaxSegs + sgi;
+    }
+    const int64_t off = ((int64_t)bh * a.N + (int64_t)kt * 128) * D;
+    for (int i = threadIdx.x; i < 128 * D / 4; i += 64) {
+      const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+      *(f32x4*)(a.dKacc + off + 4 * i) = z;
+      *(f32x4*)(a.dVacc + off + 4 * i) = z;
+    }
+  }
+}
+
+// Block-sparse finish: dK, dV of the split columns, fp32 accumulators -> 16-bit outputs.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void sparse_finish_kernel(const KArgs a) {
+  typedef typename Vec<T>::x4 T4;
+  const int item = blockIdx.x;
+  if (a.colcnt[item] <= kHeavyBlocks) return;
+  const int n_kt = a.T;
+  const int bh = item / n_kt, kt = item % n_kt;
+  const int64_t head_off = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
+  const int64_t acc_off = ((int64_t)bh * a.N + (int64_t)kt * 128) * D;
+  for (int i = threadIdx.x; i < 128 * D / 4; i += 256) {
+    const int row = (4 * i) / D, colx = (4 * i) % D;
+    const f32x4 k4 = *(const f32x4*)(a.dKacc + acc_off + 4 * i);
+    const f32x4 v4 = *(const f32x4*)(a.dVacc + acc_off + 4 * i);
+    T4 ko, vo;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { ko[e] = (T)k4[e]; vo[e] = (T)v4[e]; }
+    const int64_t o = head_off + (int64_t)(kt * 128 + row) * a.sn + colx;
+    *(T4*)((T*)a.dK + o) = ko;
+    *(T4*)((T*)a.dV + o) = vo;
+  }
 }
 
 template <typename T, int D>
-int launch_td(const KArgs& a, bool causal, bool dropout, bool sparse, hipStream_t s) {
-  const dim3 grid(kXcds * a.chunk), block(NT);
+int launch_td(KArgs a, bool causal, bool dropout, bool sparse, hipStream_t s) {
+  const int cols = a.B * a.H * a.T;
+  if (sparse) {
+    a.causal = causal;
+    hipLaunchKernelGGL((sparse_prep_kernel<D>), dim3(cols), dim3(64), 0, s, a);
+    const int e = (int)hipGetLastError();
+    if (e != 0) return e;
+  }
+  // block-sparse: kListGroups extra workgroups walk the list of heavy-column segments
+  const dim3 grid(kXcds * a.chunk + (sparse ? kListGroups : 0)), block(NT);
 #define ATTN_DKV_CASE(C, P, S)                                                    \
   if (causal == C && dropout == P && sparse == S) {                               \
     hipLaunchKernelGGL((dkv_rs_kernel<T, D, C, P, S>), grid, block, 0, s, a);     \
-    return (int)hipGetLastError();                                                \
+    int e = (int)hipGetLastError();                                               \
+    if (e == 0 && S) {                                                            \
+      hipLaunchKernelGGL((sparse_finish_kernel<T, D>), dim3(cols), dim3(256), 0, s, a); \
+      e = (int)hipGetLastError();                                                 \
+    }                                                                             \
+    return e;                                                                     \
   }
   ATTN_DKV_CASE(false, false, false)
   ATTN_DKV_CASE(true, false, false)

@@ -23,6 +23,11 @@ struct KArgs {
   const void* dO;          // bwd in
   void* dQ; void* dK; void* dV;   // bwd out
   float* Dvec;             // bwd scratch: D_i = rowsum(dO_i o O_i)   [B,H,N]
+  int* colcnt;             // block-sparse bwd scratch: kept blocks per mask column   [B*H, T]
+  int* seglist;            // block-sparse bwd scratch: [0] = number of entries, then (column * kMaxSegs + segment)
+  float* dKacc;            // block-sparse bwd scratch: fp32 dK / dV of the columns that are
+  float* dVacc;            //   split over several workgroups                         [B,H,N,d]
+  int causal;              // causal flag for the kernels that are not specialised on it
   const uint8_t* mask;     // block mask [T,T] (per head if mask_sh != 0) or nullptr
   int64_t mask_sh;
   int64_t sb, sh, sn;      // element strides of the [B,H,N,d] tensors
@@ -38,6 +43,9 @@ struct KArgs {
 };
 
 enum { kXcds = 8, kMaskBlock = 128 };
+// Block-sparse dK/dV: a mask column with more than kHeavyBlocks kept blocks is split into
+// segments of about kSegBlocks blocks (at most kMaxSegs), one workgroup each, summed with fp32 atomics.
+enum { kHeavyBlocks = 24, kSegBlocks = 12, kMaxSegs = 32 };
 
 // Launchers (defined in the .hip files).  dtype: 0 fp16, 1 bf16.  Return hipError_t as int.
 int launch_fwd(const KArgs& a, int dtype, int d, bool causal, bool dropout, bool sparse, hipStream_t s);
@@ -109,31 +117,41 @@ template <int D> __device__ __forceinline__ int lds_off(int row, int chunk) {
 // Iterates, in increasing order, over the 64-wide tiles a workgroup must visit.
 // Dense: first .. limit-1 (in tiles).  Sparse: the two 64-wide halves of every 128-block b in
 // [first, limit) with mask[b * stride] != 0.  All state is wavefront-uniform.
+// Sparse only: the first `skip` kept blocks are passed over and at most `take` are delivered.
 template <bool SPARSE> struct TileIter {
   const uint8_t* mask;
   int64_t stride;
-  int limit, pos, base, half;
+  int limit, pos, base, half, skip, take;
   uint64_t bits;
-  __device__ __forceinline__ void init(const uint8_t* m, int64_t st, int first, int lim) {
+  __device__ __forceinline__ void init(const uint8_t* m, int64_t st, int first, int lim,
+                                       int skip_blocks = 0, int take_blocks = 0x7fffffff) {
     mask = m; stride = st; limit = lim; pos = first; bits = 0; base = 0; half = -1;
+    skip = skip_blocks; take = take_blocks;
   }
   __device__ __forceinline__ int next() {
     if constexpr (!SPARSE) {
       return pos < limit ? pos++ : -1;
     } else {
       if (half >= 0) { const int t = half; half = -1; return t; }
-      while (bits == 0) {
-        if (pos >= limit) return -1;
-        const int blk = pos + (int)(threadIdx.x & 63);
-        const bool on = blk < limit && mask[(int64_t)blk * stride] != 0;
-        bits = __ballot(on);
-        base = pos;
-        pos += 64;
+      if (take <= 0) return -1;
+      while (true) {
+        while (bits == 0) {
+          if (pos >= limit) return -1;
+          const int blk = pos + (int)(threadIdx.x & 63);
+          const bool on = blk < limit && mask[(int64_t)blk * stride] != 0;
+          bits = __ballot(on);
+          base = pos;
+          pos += 64;
+          const int n = __builtin_popcountll(bits);
+          if (n <= skip) { skip -= n; bits = 0; }   // the whole chunk is before this segment
+        }
+        const int b = __builtin_ctzll(bits);
+        bits &= bits - 1;
+        if (skip > 0) { --skip; continue; }
+        --take;
+        half = 2 * (base + b) + 1;
+        return 2 * (base + b);
       }
-      const int b = __builtin_ctzll(bits);
-      bits &= bits - 1;
-      half = 2 * (base + b) + 1;
-      return 2 * (base + b);
     }
   }
 };

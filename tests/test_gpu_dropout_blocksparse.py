@@ -73,6 +73,23 @@ def test_blocksparse_butterfly_small(d):
     hp.assert_backward_ok(resb)
 
 
+@pytest.mark.parametrize("causal,p", [(False, 0.0), (True, 0.1)])
+def test_blocksparse_heavy_column_is_split(causal, p):
+    """T = 32: mask column 0 keeps all 32 blocks, which the dK/dV kernel splits over several
+    workgroups (fp32 atomics); the other columns take the direct path."""
+    T = 32
+    N = 128 * T
+    t, dev = hp.make_case(1, 2, N, 64, "bf16", 650)
+    bm = inputs.butterfly_block_mask(T)
+    assert int(bm[:, 0].sum()) == 32 and int(bm[:, 5].sum()) < 12
+    kw = dict(causal=causal, p=p, seed=21, offset=2, block_mask=bm)
+    res = hp.check_forward(t, dev, "bf16", 0.125, heads=[(0, 1)], **kw)
+    hp.assert_forward_ok(res)
+    resb = hp.check_backward(t, dev, "bf16", 0.125, heads=[(0, 0), (0, 1)], **kw)
+    print("heavy column bwd", causal, p, resb)
+    hp.assert_backward_ok(resb)
+
+
 def test_blocksparse_random_per_head_mask_causal_dropout_and_empty_rows():
     T = 5
     N = 128 * T

@@ -92,6 +92,11 @@ def test_null_pointers_and_workspace(lib):
     assert lib.attn_bwd(ctypes.byref(p), *args, v, need - 1) == -7                  # too small
     assert lib.attn_bwd(ctypes.byref(p), *([v] * 8 + [z]), v, need) == -1
     assert lib.attn_bwd_workspace_bytes(ctypes.byref(_params(d=7))) == 0
+    sparse_need = lib.attn_blocksparse_bwd_workspace_bytes(ctypes.byref(p))
+    assert sparse_need == 512 + 512 + 2 * 128 * 64 * 4          # D | segment list + column counts | fp32 dK, dV
+    assert lib.attn_blocksparse_bwd_workspace_bytes(ctypes.byref(_params(N=100))) == 0
+    args_m = [v, 128, 0] + [v] * 9
+    assert lib.attn_blocksparse_bwd(ctypes.byref(p), *args_m, v, need) == -7     # dense size is too small
 
 
 def test_mask_arguments(lib):
