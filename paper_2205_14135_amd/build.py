@@ -46,6 +46,11 @@ def build(verbose: bool = False, extra_flags=()) -> str:
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stdout}\n{r.stderr}")
+    # a kernel whose host stub went missing would only show up when the library is loaded
+    nm = subprocess.run(["nm", "-u", LIB], capture_output=True, text=True)
+    missing = [l.split()[-1] for l in nm.stdout.splitlines() if "attn" in l]
+    if missing:
+        raise RuntimeError("undefined symbols in the built library: " + ", ".join(missing[:5]))
     if verbose:
         print("built", LIB)
     return LIB

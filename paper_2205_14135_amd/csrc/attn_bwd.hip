@@ -63,8 +63,8 @@ template <typename T, int D, bool CAUSAL, bool DROPOUT, bool SPARSE>
 __global__ __launch_bounds__(NT, 2) void dq_kernel(const KArgs a) {
   typedef typename Vec<T>::x8 T8;
   constexpr int KK = D / 16, DB = D / 32;
-  __shared__ __attribute__((aligned(16))) T Ks[TILE * D];
-  __shared__ __attribute__((aligned(16))) T Vs[TILE * D];
+  __shared__ __attribute__((aligned(16))) T Ks[2][TILE * D];   // double buffered, filled by async copies
+  __shared__ __attribute__((aligned(16))) T Vs[2][TILE * D];
 
   const int item = xcd_item(a.n_items, a.chunk);
   if (item < 0) return;
@@ -108,17 +108,25 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const KArgs a) {
   }
   TrOffsets<D> tro;
   tro.init();
-  TileStage<T, D, NT> ks, vs;
+  TileDma<T, D, NT / 64> dma;
+  dma.init(a.sn);
 
   const float c = a.scale_log2;
   int jt = it.next();
-  if (jt >= 0) { ks.load(Kg, a.sn, jt * TILE); vs.load(Vg, a.sn, jt * TILE); }
+  int buf = 0;
+  if (jt >= 0) {
+    dma.copy(Kg + (int64_t)jt * TILE * a.sn, Ks[0]);
+    dma.copy(Vg + (int64_t)jt * TILE * a.sn, Vs[0]);
+  }
+  __syncthreads();   // tile 0 has landed (the compiler waits for the copies before the barrier)
   while (jt >= 0) {
-    ks.store(Ks);
-    vs.store(Vs);
-    __syncthreads();
     const int jn = it.next();
-    if (jn >= 0) { ks.load(Kg, a.sn, jn * TILE); vs.load(Vg, a.sn, jn * TILE); }
+    if (jn >= 0) {   // next tile streams into the other buffer while this one is used
+      dma.copy(Kg + (int64_t)jn * TILE * a.sn, Ks[buf ^ 1]);
+      dma.copy(Vg + (int64_t)jn * TILE * a.sn, Vs[buf ^ 1]);
+    }
+    const T* Kt = Ks[buf];
+    const T* Vt = Vs[buf];
 
     const int k0 = jt * TILE;
     if (!CAUSAL || k0 <= q0 + 31) {
@@ -132,8 +140,8 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const KArgs a) {
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
           const int off = lds_off<D>(32 * kb + r, 2 * kk + g);
-          s[kb] = mfma32(*(const T8*)(Ks + off), qf[kk], s[kb]);     // S^T  = K Q^T
-          dp[kb] = mfma32(*(const T8*)(Vs + off), gf[kk], dp[kb]);   // dP^T = V dO^T
+          s[kb] = mfma32(*(const T8*)(Kt + off), qf[kk], s[kb]);     // S^T  = K Q^T
+          dp[kb] = mfma32(*(const T8*)(Vt + off), gf[kk], dp[kb]);   // dP^T = V dO^T
         }
       // P = exp(S - L); dS = P o (dP o Z - D)
 #pragma unroll
@@ -165,14 +173,17 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const KArgs a) {
       for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int cc = 0; cc < 4; ++cc) {
-          const T* base = Ks + 16 * cc * D;
+          const T* base = Kt + 16 * cc * D;
           dq[db] = mfma32(tr_frag<T8>(base + tro.off[db][0], base + tro.off[db][1]), dsf[cc], dq[db]);
         }
     }
-    __syncthreads();
+    __syncthreads();   // next tile has landed, and everyone is done with this buffer
     jt = jn;
+    buf ^= 1;
   }
-  store_rows<T, D>((T*)a.dQ + head_off + (int64_t)qi * a.sn, dq, a.tau, g);
+  // the loop ends on a barrier (or never touched LDS): the tile buffers stage the output rows
+  T* stage = (wave < 2 ? &Ks[0][0] + wave * 32 * D : &Vs[0][0] + (wave - 2) * 32 * D);
+  store_rows_coalesced<T, D>(stage, (T*)a.dQ + head_off + (int64_t)q0 * a.sn, a.sn, dq, a.tau);
 }
 
 // ---------------------------------------------------------------------------------------------

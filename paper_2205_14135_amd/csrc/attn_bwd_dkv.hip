@@ -121,27 +121,49 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
 
   const float c = a.scale_log2;
 
+  // LDS operand reads run PF fragments ahead of the MFMA that consumes them (the scheduling
+  // barriers keep the compiler from shortening that distance), so the matrix pipe does not wait
+  // for LDS latency on every instruction.
+  constexpr int PF = 4;
   // product of a row-read tile with the register fragments: sd[qb] = Tile[32 qb .. +31][:] . kvf
   auto row_product = [&](const T* tile) {
+    auto frag = [&](int f) { return *(const T8*)(tile + lds_off<D>(32 * (f & 1) + r, 2 * (f >> 1) + g)); };  // f = 2 kk + qb
+    T8 ring[PF];
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb)
+    for (int f = 0; f < PF; ++f) ring[f] = frag(f);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int i = 0; i < 16; ++i) sd[qb][i] = 0.f;
+    for (int f = 0; f < 2 * KK; ++f) {
+      const T8 cur = ring[f % PF];
+      if (f < 2) {
+        f32x16 z;
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk)
-#pragma unroll
-      for (int qb = 0; qb < 2; ++qb)
-        sd[qb] = mfma32(*(const T8*)(tile + lds_off<D>(32 * qb + r, 2 * kk + g)), kvf[kk], sd[qb]);
+        for (int i = 0; i < 16; ++i) z[i] = 0.f;
+        sd[f & 1] = mfma32(cur, kvf[f >> 1], z);
+      } else {
+        sd[f & 1] = mfma32(cur, kvf[f >> 1], sd[f & 1]);
+      }
+      if (f + PF < 2 * KK) ring[f % PF] = frag(f + PF);
+      __builtin_amdgcn_sched_barrier(0);
+    }
   };
   // acc^T += Tile^T . frag   (contraction over the 64 queries of the tile)
-  auto col_product = [&](const T* tile, const T8 (&frag)[4]) {
+  auto col_product = [&](const T* tile, const T8 (&bfrag)[4]) {
+    auto frag = [&](int f) {   // f = DB cc + db: consecutive MFMAs hit different accumulators
+      const T* base = tile + 16 * (f / DB) * D;
+      return tr_frag<T8>(base + tro.off[f % DB][0], base + tro.off[f % DB][1]);
+    };
+    T8 ring[PF];
 #pragma unroll
-    for (int cc = 0; cc < 4; ++cc)
+    for (int f = 0; f < PF; ++f) ring[f] = frag(f);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        const T* base = tile + 16 * cc * D;
-        acc[db] = mfma32(tr_frag<T8>(base + tro.off[db][0], base + tro.off[db][1]), frag[cc], acc[db]);
-      }
+    for (int f = 0; f < 4 * DB; ++f) {
+      const T8 cur = ring[f % PF];
+      acc[f % DB] = mfma32(cur, bfrag[f / DB], acc[f % DB]);
+      if (f + PF < 4 * DB) ring[f % PF] = frag(f + PF);
+      __builtin_amdgcn_sched_barrier(0);
+    }
   };
   auto keep_from_word = [&](uint32_t mine, uint32_t (&keep_from)[4]) {
     // bits drawn by the quad lane that handled query e, shifted so that bit 4n is this lane's key
@@ -263,7 +285,10 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
       for (int i = 0; i < 16; ++i)
         unsafeAtomicAdd(dst + 32 * db + 8 * (i >> 2) + 4 * g + (i & 3), acc[db][i] * out_scale);
   } else {
-    store_rows<T, D>((T*)(role_b ? a.dK : a.dV) + head_off + (int64_t)kj * a.sn, acc, out_scale, g);
+    __syncthreads();   // role B has finished reading the tiles: they stage the output rows
+    T* stage = (role_b ? &Gs[0][0] : &Qs[0][0]) + pair * 32 * D;
+    store_rows_coalesced<T, D>(stage, (T*)(role_b ? a.dK : a.dV) + head_off + (int64_t)kw0 * a.sn, a.sn, acc,
+                               out_scale);
   }
   if (!list_mode) return;
   __syncthreads();   // LDS is reused by the next segment

@@ -15,6 +15,7 @@
 // probabilities are already in the B-operand layout of the second product O^T = V^T P^T.
 // V^T fragments come from the row-major V tile in LDS through the gfx950 transposing LDS read.
 #include "attn_common.h"
+#include "attn_tiles.h"
 
 #include <cstdlib>
 
@@ -228,16 +229,9 @@ __global__ __launch_bounds__(NT, 2) void fwd_kernel(const KArgs a) {
         *(f32x4*)(Og + 32 * db + 8 * i4 + 4 * g) = v;
       }
   } else {
-    T* Og = (T*)a.O + head_off + (int64_t)qi * a.sn;
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int i4 = 0; i4 < 4; ++i4) {
-        T4 v;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = (T)(o[db][4 * i4 + e] * inv);
-        *(T4*)(Og + 32 * db + 8 * i4 + 4 * g) = v;
-      }
+    // coalesced row stores through the (now idle) tile buffers: two wavefronts per buffer
+    T* stage = (wave < 2 ? Ks + wave * 32 * D : Vs + (wave - 2) * 32 * D);
+    store_rows_coalesced<T, D>(stage, (T*)a.O + head_off + (int64_t)q0 * a.sn, a.sn, o, inv);
   }
 }
 

@@ -15,6 +15,7 @@
 // slots 2t, 2t+1.  Every wavefront stages 1/8 of each tile (global -> registers -> LDS): it stores
 // its share of K(j+1) and V(j) at the start of its own M(j), inside both windows for either group.
 #include "attn_common.h"
+#include "attn_tiles.h"
 
 namespace attn {
 namespace {
@@ -236,6 +237,8 @@ __global__ __launch_bounds__(NT) void fwd_pp_kernel(const KArgs a) {
   }
   do_M(active(J - 1), J - 1, false, 0);
   if (!group_b) { __builtin_amdgcn_sched_barrier(0); __syncthreads(); }  // equal barrier counts
+  __builtin_amdgcn_sched_barrier(0);
+  __syncthreads();   // every wavefront is done with the tiles: the buffers become output staging
 
   if (!valid) return;
   const float l_tot = l_run + xchg32(l_run);
@@ -256,16 +259,8 @@ __global__ __launch_bounds__(NT) void fwd_pp_kernel(const KArgs a) {
         *(f32x4*)(Og + 32 * db + 8 * i4 + 4 * g) = v;
       }
   } else {
-    T* Og = (T*)a.O + head_off + (int64_t)qi * a.sn;
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int i4 = 0; i4 < 4; ++i4) {
-        T4 v;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = (T)(o[db][4 * i4 + e] * inv);
-        *(T4*)(Og + 32 * db + 8 * i4 + 4 * g) = v;
-      }
+    T* stage = wave < 4 ? &Ks[0][0] + wave * 32 * D : &Vs[0][0] + (wave - 4) * 32 * D;
+    store_rows_coalesced<T, D>(stage, (T*)a.O + head_off + (int64_t)q0 * a.sn, a.sn, o, inv);
   }
 }
 

@@ -24,6 +24,36 @@ template <typename T, int D, int NT> struct TileStage {
   }
 };
 
+// Asynchronous copy of a [64][D] tile from global memory straight into swizzled LDS (no register
+// staging, no LDS store instructions): each global_load_lds_dwordx4 moves 64 lanes x 16 bytes to
+// 1 KB of consecutive LDS, so lane l of copy q lands on row q*(64/CPR) + l/CPR, physical chunk
+// l%CPR, and therefore fetches the logical chunk (l%CPR) ^ swizzle(row) of that row.  The NW
+// wavefronts of the workgroup issue (D/8)/NW copies each.  Completion is counted by vmcnt: the
+// compiler waits for it before the next workgroup barrier.
+template <typename T, int D, int NW> struct TileDma {
+  static constexpr int CPR = D / 8, RPC = 64 / CPR, NCOPY = D / 8, PER_WAVE = NCOPY / NW;
+  static_assert(NCOPY % NW == 0, "copies must divide evenly over the wavefronts");
+  int64_t goff[PER_WAVE];   // element offset of this lane's chunk inside a tile whose row 0 is at 0
+  __device__ __forceinline__ void init(int64_t sn) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int p = 0; p < PER_WAVE; ++p) {
+      const int row = (wave * PER_WAVE + p) * RPC + lane / CPR;
+      goff[p] = (int64_t)row * sn + 8 * ((lane % CPR) ^ swz_bits<D>(row));
+    }
+  }
+  __device__ __forceinline__ void copy(const T* g_row0, T* lds_tile) const {
+    const int wave = threadIdx.x >> 6;
+#if defined(__HIP_DEVICE_COMPILE__)   // the builtin exists in the device pass only
+#pragma unroll
+    for (int p = 0; p < PER_WAVE; ++p)
+      __builtin_amdgcn_global_load_lds(g_row0 + goff[p], lds_tile + (wave * PER_WAVE + p) * 512, 16, 0, 0);
+#else
+    (void)g_row0; (void)lds_tile; (void)wave;
+#endif
+  }
+};
+
 // Per-lane LDS offsets for the transposing read of a swizzled tile (see attn_fwd.hip for the
 // access pattern): off[db][hi] addresses rows 4g + t (+8 if hi) of a 16-row chunk, d block db.
 template <int D> struct TrOffsets {
@@ -66,5 +96,37 @@ __device__ __forceinline__ void store_rows(T* dst_row, const f32x16 (&acc)[D / 3
     }
 }
 
+
+// Same result as store_rows for the 32 tokens of a wavefront, but through a wavefront-private
+// LDS area of 32 * D elements so that global memory sees whole 16-byte-per-lane row segments
+// (a token row is written by D/8 consecutive lanes) instead of 8-byte pieces 2*D bytes apart.
+// The area is unpadded; the 16-byte chunk index is XORed with the row to spread the banks.
+// dst_row0 points at the row of the wavefront's first token.
+template <typename T, int D>
+__device__ __forceinline__ void store_rows_coalesced(T* stage, T* dst_row0, int64_t sn,
+                                                     const f32x16 (&acc)[D / 32], float scale) {
+  typedef typename Vec<T>::x4 T4;
+  typedef typename Vec<T>::x8 T8;
+  constexpr int CPR = D / 8;         // 16-byte chunks per row
+  constexpr int RPP = 64 / CPR;      // rows per pass of the read-back
+  const int lane = threadIdx.x & 63, r = lane & 31, g = lane >> 5;
+#pragma unroll
+  for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+    for (int i4 = 0; i4 < 4; ++i4) {
+      T4 v;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = (T)(acc[db][4 * i4 + e] * scale);
+      const int chunk = (4 * db + i4) ^ (r & (CPR - 1));
+      *(T4*)(stage + r * D + 8 * chunk + 4 * g) = v;
+    }
+  __builtin_amdgcn_wave_barrier();   // same wavefront: LDS operations complete in program order
+#pragma unroll
+  for (int p = 0; p < 32 / RPP; ++p) {
+    const int row = p * RPP + lane / CPR, ch = lane % CPR;
+    const T8 v = *(const T8*)(stage + row * D + 8 * (ch ^ (row & (CPR - 1))));
+    *(T8*)(dst_row0 + (int64_t)row * sn + 8 * ch) = v;
+  }
+}
 
 }  // namespace attn
