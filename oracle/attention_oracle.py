@@ -29,6 +29,8 @@ notes of the repository):
   * block mask: entry (i, j) is visible iff block_mask[i // blk, j // blk] != 0
     (Section 3.3), and it is ANDed with the causal mask when both are given;
   * a row with no visible key yields O = 0, L = -inf and zero gradients;
+  * key-padding mask: per-batch length; tokens at positions >= length neither attend nor are
+    attended to (their O is 0, L is -inf, and every gradient at those positions is 0);
   * the saved statistic is one number per row, L = m + ln(l); P = exp(S - L)
     equals diag(l)^-1 exp(S - m) of Algorithm 4;
   * the dropout generator is Philox-4x32-10 (Salmon et al., SC'11), see
@@ -129,13 +131,18 @@ def dropout_keep_mask(b, h, H, N, p_drop, seed, offset, rows=None):
     return words >= np.uint32(thr) if thr <= 0xFFFFFFFF else np.zeros_like(words, bool)
 
 
-def visible_mask(N, causal=False, block_mask=None, mask_block=128, rows=None):
-    """Boolean [len(rows), N]: True where key j may be attended by query i."""
+def visible_mask(N, causal=False, block_mask=None, mask_block=128, rows=None, key_length=None):
+    """Boolean [len(rows), N]: True where key j may be attended by query i.
+
+    key_length (the key-padding mask named as the example of MASK in Appendix B.3): tokens at
+    positions >= key_length are padding; they are neither attended to nor do they attend."""
     if rows is None:
         rows = np.arange(N)
     rows = np.asarray(rows, dtype=np.int64)
     vis = np.ones((rows.size, N), dtype=bool)
     j = np.arange(N, dtype=np.int64)[None, :]
+    if key_length is not None:
+        vis &= (j < int(key_length)) & (rows[:, None] < int(key_length))
     if causal:
         vis &= j <= rows[:, None]
     if block_mask is not None:
@@ -169,7 +176,7 @@ def _dropout_factor(p_drop, keep, shape):
 
 
 def forward_head(Q, K, V, tau, *, causal=False, p_drop=0.0, keep=None,
-                 block_mask=None, mask_block=128, rows=None, return_p=False):
+                 block_mask=None, mask_block=128, rows=None, return_p=False, key_length=None):
     """Forward for one head.  Q, K, V: [N, d].  keep: bool [len(rows), N] or None.
 
     rows: optional query indices; only those rows of O and L are computed and
@@ -183,7 +190,7 @@ def forward_head(Q, K, V, tau, *, causal=False, p_drop=0.0, keep=None,
     if rows is None:
         rows = np.arange(N)
     rows = np.asarray(rows, dtype=np.int64)
-    vis = visible_mask(N, causal, block_mask, mask_block, rows)
+    vis = visible_mask(N, causal, block_mask, mask_block, rows, key_length)
     P, L = _probabilities(Q[rows], K, float(tau), vis)
     Z = _dropout_factor(p_drop, keep, P.shape)
     O = (P * Z) @ V
@@ -193,7 +200,7 @@ def forward_head(Q, K, V, tau, *, causal=False, p_drop=0.0, keep=None,
 
 
 def backward_head(Q, K, V, dO, tau, *, causal=False, p_drop=0.0, keep=None,
-                  block_mask=None, mask_block=128, rows=None):
+                  block_mask=None, mask_block=128, rows=None, key_length=None):
     """Backward for one head: returns dQ [R, d], dK [N, d], dV [N, d].
 
     rows: optional query indices.  dQ is returned for those rows only, and dK,
@@ -209,7 +216,7 @@ def backward_head(Q, K, V, dO, tau, *, causal=False, p_drop=0.0, keep=None,
     if rows is None:
         rows = np.arange(N)
     rows = np.asarray(rows, dtype=np.int64)
-    vis = visible_mask(N, causal, block_mask, mask_block, rows)
+    vis = visible_mask(N, causal, block_mask, mask_block, rows, key_length)
     P, _ = _probabilities(Q[rows], K, tau, vis)
     Z = _dropout_factor(p_drop, keep, P.shape)
     dV = (P * Z).T @ dO[rows]
@@ -233,7 +240,7 @@ def _head_block_mask(block_mask, b, h, H):
 
 
 def attention_forward(Q, K, V, tau, *, causal=False, p_drop=0.0, seed=0, offset=0,
-                      block_mask=None, mask_block=128, heads=None):
+                      block_mask=None, mask_block=128, heads=None, key_lengths=None):
     """Batched forward.  Q, K, V: [B, H, N, d] (any float dtype; widened exactly).
 
     heads: optional list of (b, h) pairs to compute; other heads are left NaN.
@@ -247,12 +254,13 @@ def attention_forward(Q, K, V, tau, *, causal=False, p_drop=0.0, seed=0, offset=
         keep = dropout_keep_mask(b, h, H, N, p_drop, seed, offset) if p_drop > 0 else None
         O[b, h], L[b, h] = forward_head(
             Q[b, h], K[b, h], V[b, h], tau, causal=causal, p_drop=p_drop, keep=keep,
-            block_mask=_head_block_mask(block_mask, b, h, H), mask_block=mask_block)
+            block_mask=_head_block_mask(block_mask, b, h, H), mask_block=mask_block,
+            key_length=None if key_lengths is None else key_lengths[b])
     return O, L
 
 
 def attention_backward(Q, K, V, dO, tau, *, causal=False, p_drop=0.0, seed=0, offset=0,
-                       block_mask=None, mask_block=128, heads=None):
+                       block_mask=None, mask_block=128, heads=None, key_lengths=None):
     """Batched backward: returns dQ, dK, dV as float64 [B, H, N, d]."""
     B, H, N, d = Q.shape
     dQ = np.full((B, H, N, d), np.nan)
@@ -263,5 +271,6 @@ def attention_backward(Q, K, V, dO, tau, *, causal=False, p_drop=0.0, seed=0, of
         keep = dropout_keep_mask(b, h, H, N, p_drop, seed, offset) if p_drop > 0 else None
         dQ[b, h], dK[b, h], dV[b, h] = backward_head(
             Q[b, h], K[b, h], V[b, h], dO[b, h], tau, causal=causal, p_drop=p_drop, keep=keep,
-            block_mask=_head_block_mask(block_mask, b, h, H), mask_block=mask_block)
+            block_mask=_head_block_mask(block_mask, b, h, H), mask_block=mask_block,
+            key_length=None if key_lengths is None else key_lengths[b])
     return dQ, dK, dV

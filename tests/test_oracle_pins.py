@@ -360,6 +360,30 @@ def test_batched_wrappers_route_heads_and_masks():
             np.testing.assert_array_equal(dV[b, h], g[2])
 
 
+# ------------------------------------------------------------ padding mask --
+@pytest.mark.parametrize("causal", [False, True])
+def test_key_padding_equals_the_truncated_problem(causal):
+    """With key_length = n the valid part is exactly attention on the first n tokens, and the
+    padding part is zero (O, gradients) / -inf (L)."""
+    N, d, n = 16, 4, 11
+    Q, K, V, dO = (rnd(N, d, seed=s) for s in (81, 82, 83, 84))
+    keep = orc.dropout_keep_mask(0, 0, 1, N, 0.2, 5, 0)
+    kw = dict(causal=causal, p_drop=0.2)
+    O, L = orc.forward_head(Q, K, V, 0.5, keep=keep, key_length=n, **kw)
+    g = orc.backward_head(Q, K, V, dO, 0.5, keep=keep, key_length=n, **kw)
+    Ot, Lt = orc.forward_head(Q[:n], K[:n], V[:n], 0.5, keep=keep[:n, :n], **kw)
+    gt = orc.backward_head(Q[:n], K[:n], V[:n], dO[:n], 0.5, keep=keep[:n, :n], **kw)
+    np.testing.assert_allclose(O[:n], Ot, atol=1e-14)
+    np.testing.assert_allclose(L[:n], Lt, atol=1e-14)
+    assert (O[n:] == 0).all() and np.isneginf(L[n:]).all()
+    for a, b in zip(g, gt):
+        np.testing.assert_allclose(a[:n], b, atol=1e-14)
+        assert (a[n:] == 0).all()
+    # length 0: everything is padding
+    O0, L0 = orc.forward_head(Q, K, V, 0.5, key_length=0)
+    assert (O0 == 0).all() and np.isneginf(L0).all()
+
+
 # ------------------------------------------------------------------- inputs --
 def test_bf16_rounding_is_nearest_even():
     import torch
