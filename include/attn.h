@@ -75,6 +75,12 @@ typedef struct {
   int32_t o_fp32;            /* != 0: O is read/written as float32 [B,H,N,d] packed
                                 with the same strides, instead of dtype      */
   void* stream;              /* hipStream_t, borrowed for the call           */
+  const int32_t* key_lengths; /* NULL, or device int32 [B]: key-padding mask (the MASK example of
+                                Appendix B.3).  Tokens of batch b at positions >= key_lengths[b]
+                                are padding: they are not attended to, their O is 0, their LSE
+                                -inf and all gradients at those positions are 0.  Lengths are clamped to [0, N].
+                                Sequences of any length are run by padding N up to a multiple
+                                of 128 and passing the true lengths here.                    */
 } attn_params;
 
 /*

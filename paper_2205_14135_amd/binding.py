@@ -35,6 +35,7 @@ class AttnParams(ctypes.Structure):
         ("seed", ctypes.c_uint64), ("offset", ctypes.c_uint64),
         ("o_fp32", ctypes.c_int32),
         ("stream", ctypes.c_void_p),
+        ("key_lengths", ctypes.c_void_p),
     ]
 
 
@@ -100,7 +101,8 @@ def _dtype_code(t: torch.Tensor) -> int:
 
 
 def make_params(Q: torch.Tensor, softmax_scale: float, causal: bool = False, dropout_p: float = 0.0,
-                seed: int = 0, offset: int = 0, o_fp32: bool = False, stream=None) -> AttnParams:
+                seed: int = 0, offset: int = 0, o_fp32: bool = False, stream=None,
+                key_lengths: Optional[torch.Tensor] = None) -> AttnParams:
     """Params for [B,H,N,d] tensors laid out like Q (d contiguous)."""
     if Q.dim() != 4 or Q.stride(3) != 1:
         raise ValueError("expected a [B,H,N,d] tensor with contiguous last axis")
@@ -118,6 +120,10 @@ def make_params(Q: torch.Tensor, softmax_scale: float, causal: bool = False, dro
     p.offset = int(offset) & 0xFFFFFFFFFFFFFFFF
     p.o_fp32 = int(bool(o_fp32))
     p.stream = ctypes.c_void_p(int(stream))
+    if key_lengths is not None:
+        if key_lengths.dtype != torch.int32 or key_lengths.shape != (B,) or not key_lengths.is_contiguous():
+            raise TypeError("key_lengths must be a contiguous int32 tensor of shape [B]")
+        p.key_lengths = ctypes.c_void_p(key_lengths.data_ptr())
     return p
 
 
@@ -147,10 +153,10 @@ def _mask_args(block_mask: torch.Tensor, H: int):
 
 
 def attn_fwd(Q, K, V, *, softmax_scale, causal=False, dropout_p=0.0, seed=0, offset=0,
-             o_fp32=False, out=None, lse=None, stream=None) -> Tuple[torch.Tensor, torch.Tensor]:
+             o_fp32=False, out=None, lse=None, stream=None, key_lengths=None) -> Tuple[torch.Tensor, torch.Tensor]:
     """O, LSE = attention forward.  Outputs are allocated with torch unless given."""
     _same_layout(Q, K, V)
-    p = make_params(Q, softmax_scale, causal, dropout_p, seed, offset, o_fp32, stream)
+    p = make_params(Q, softmax_scale, causal, dropout_p, seed, offset, o_fp32, stream, key_lengths)
     B, H, N, d = Q.shape
     if out is None:
         out = torch.empty_strided(Q.shape, Q.stride(), dtype=torch.float32 if o_fp32 else Q.dtype,
@@ -177,10 +183,10 @@ def _workspace(p: AttnParams, device, workspace, sparse=False):
 
 
 def attn_bwd(Q, K, V, O, dO, LSE, *, softmax_scale, causal=False, dropout_p=0.0, seed=0, offset=0,
-             o_fp32=False, workspace=None, grads=None, stream=None):
+             o_fp32=False, workspace=None, grads=None, stream=None, key_lengths=None):
     """dQ, dK, dV = attention backward (O, LSE from attn_fwd with the same options)."""
     _same_layout(Q, K, V, dO)
-    p = make_params(Q, softmax_scale, causal, dropout_p, seed, offset, o_fp32, stream)
+    p = make_params(Q, softmax_scale, causal, dropout_p, seed, offset, o_fp32, stream, key_lengths)
     if grads is None:
         grads = tuple(torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device)
                       for _ in range(3))
@@ -192,9 +198,10 @@ def attn_bwd(Q, K, V, O, dO, LSE, *, softmax_scale, causal=False, dropout_p=0.0,
 
 
 def attn_blocksparse_fwd(Q, K, V, block_mask, *, softmax_scale, mask_block=128, causal=False,
-                         dropout_p=0.0, seed=0, offset=0, o_fp32=False, out=None, lse=None, stream=None):
+                         dropout_p=0.0, seed=0, offset=0, o_fp32=False, out=None, lse=None, stream=None,
+                         key_lengths=None):
     _same_layout(Q, K, V)
-    p = make_params(Q, softmax_scale, causal, dropout_p, seed, offset, o_fp32, stream)
+    p = make_params(Q, softmax_scale, causal, dropout_p, seed, offset, o_fp32, stream, key_lengths)
     B, H, N, d = Q.shape
     msh = _mask_args(block_mask, H)
     if out is None:
@@ -210,9 +217,9 @@ def attn_blocksparse_fwd(Q, K, V, block_mask, *, softmax_scale, mask_block=128, 
 
 def attn_blocksparse_bwd(Q, K, V, O, dO, LSE, block_mask, *, softmax_scale, mask_block=128, causal=False,
                          dropout_p=0.0, seed=0, offset=0, o_fp32=False, workspace=None, grads=None,
-                         stream=None):
+                         stream=None, key_lengths=None):
     _same_layout(Q, K, V, dO)
-    p = make_params(Q, softmax_scale, causal, dropout_p, seed, offset, o_fp32, stream)
+    p = make_params(Q, softmax_scale, causal, dropout_p, seed, offset, o_fp32, stream, key_lengths)
     msh = _mask_args(block_mask, Q.shape[1])
     if grads is None:
         grads = tuple(torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device)
@@ -228,11 +235,11 @@ def attn_blocksparse_bwd(Q, K, V, O, dO, LSE, block_mask, *, softmax_scale, mask
 
 def attn_bwd_timed(Q, K, V, O, dO, LSE, events, *, softmax_scale, block_mask=None, mask_block=128,
                    causal=False, dropout_p=0.0, seed=0, offset=0, o_fp32=False, workspace=None,
-                   grads=None, stream=None):
+                   grads=None, stream=None, key_lengths=None):
     """attn_bwd / attn_blocksparse_bwd that also records four caller-owned hipEvent_t handles
     (ints) on the stream: before, after row-dot, after dQ, after dK/dV."""
     _same_layout(Q, K, V, dO)
-    p = make_params(Q, softmax_scale, causal, dropout_p, seed, offset, o_fp32, stream)
+    p = make_params(Q, softmax_scale, causal, dropout_p, seed, offset, o_fp32, stream, key_lengths)
     msh = 0 if block_mask is None else _mask_args(block_mask, Q.shape[1])
     if grads is None:
         grads = tuple(torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device)

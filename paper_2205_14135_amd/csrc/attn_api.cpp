@@ -9,7 +9,7 @@ namespace {
 
 constexpr int kVersion = 100;  // 0.1.0
 
-static_assert(sizeof(attn_params) == 96, "attn_params layout is part of the ABI");
+static_assert(sizeof(attn_params) == 104, "attn_params layout is part of the ABI");
 
 struct Checked {
   attn::KArgs k;
@@ -52,6 +52,7 @@ int check_params(const attn_params* p, Checked* out) {
   k.seed_hi = (uint32_t)(p->seed >> 32);
   k.offset_lo = (uint32_t)(p->offset & 0xFFFFFFFFu);
   k.o_fp32 = p->o_fp32 != 0;
+  k.klen = p->key_lengths;
   out->dtype = p->dtype;
   out->d = p->d;
   out->causal = p->causal != 0;

@@ -99,11 +99,14 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const KArgs a) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) dq[db][i] = 0.f;
 
+  // key-padding mask: keys >= len contribute nothing (rows >= len have LSE = -inf, hence P = 0)
+  const int len = a.klen ? min(max(a.klen[b], 0), a.N) : a.N;
   TileIter<SPARSE> it;
   {
     int lim;
-    if constexpr (SPARSE) lim = CAUSAL ? qt + 1 : a.T;
-    else lim = CAUSAL ? 2 * qt + 2 : a.N / TILE;
+    if constexpr (SPARSE) lim = min(CAUSAL ? qt + 1 : a.T, (len + 127) / 128);
+    else lim = min(CAUSAL ? 2 * qt + 2 : a.N / TILE, (len + TILE - 1) / TILE);
+    if (qt * 128 >= len) lim = 0;
     it.init(SPARSE ? a.mask + (int64_t)h * a.mask_sh + (int64_t)qt * a.T : nullptr, 1, 0, lim);
   }
   TrOffsets<D> tro;
@@ -143,6 +146,13 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const KArgs a) {
           s[kb] = mfma32(*(const T8*)(Kt + off), qf[kk], s[kb]);     // S^T  = K Q^T
           dp[kb] = mfma32(*(const T8*)(Vt + off), gf[kk], dp[kb]);   // dP^T = V dO^T
         }
+      if (k0 + TILE > len) {   // the tile holds padded keys: their logits become -inf, hence P = 0
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int i = 0; i < 16; ++i)
+            if (k0 + 32 * kb + 8 * (i >> 2) + 4 * g + (i & 3) >= len) s[kb][i] = -INFINITY;
+      }
       // P = exp(S - L); dS = P o (dP o Z - D)
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
@@ -227,11 +237,12 @@ __global__ __launch_bounds__(NT, 1) void dkv_kernel(const KArgs a) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) { dk[db][i] = 0.f; dv[db][i] = 0.f; }
 
+  const int len = a.klen ? min(max(a.klen[b], 0), a.N) : a.N;   // key-padding mask
   TileIter<SPARSE> it;
   if constexpr (SPARSE)
-    it.init(a.mask + (int64_t)h * a.mask_sh + kt, a.T, CAUSAL ? kt : 0, a.T);
+    it.init(a.mask + (int64_t)h * a.mask_sh + kt, a.T, CAUSAL ? kt : 0, kt * 128 >= len ? 0 : min(a.T, (len + 127) / 128));
   else
-    it.init(nullptr, 0, CAUSAL ? 2 * kt : 0, a.N / TILE);
+    it.init(nullptr, 0, CAUSAL ? 2 * kt : 0, kt * 128 >= len ? 0 : min(a.N / TILE, (len + TILE - 1) / TILE));
   TrOffsets<D> tro;
   tro.init();
   TileStage<T, D, NT> qs, gs;
@@ -300,7 +311,7 @@ __global__ __launch_bounds__(NT, 1) void dkv_kernel(const KArgs a) {
           for (int e = 0; e < 4; ++e) {
             const int i = 4 * i4 + e;
             float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[qb][i], c, -l4[e]));
-            if (CAUSAL && kj > i0 + 32 * qb + 8 * i4 + 4 * g + e) p = 0.f;
+            if ((CAUSAL && kj > i0 + 32 * qb + 8 * i4 + 4 * g + e) || kj >= len) p = 0.f;
             float dpv = dp[qb][i];
             float pk = p;
             if constexpr (DROPOUT) {

@@ -95,11 +95,15 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
     for (int i = 0; i < 16; ++i) acc[db][i] = 0.f;
   f32x16 sd[2];    // role A: S, role B: dP   (rows = queries of the tile, column = key)
 
+  // key-padding mask: key blocks and query tiles at or beyond the batch's length are not visited
+  // (rows >= len inside the last tile have LSE = -inf, hence P = 0); masked keys get P = 0
+  const int len = a.klen ? min(max(a.klen[b], 0), a.N) : a.N;
   TileIter<SPARSE> it;
   if constexpr (SPARSE)
-    it.init(a.mask + (int64_t)h * a.mask_sh + kt, a.T, CAUSAL ? kt : 0, a.T, skip_blocks, take_blocks);
+    it.init(a.mask + (int64_t)h * a.mask_sh + kt, a.T, CAUSAL ? kt : 0,
+            kt * 128 >= len ? 0 : min(a.T, (len + 127) / 128), skip_blocks, take_blocks);
   else
-    it.init(nullptr, 0, CAUSAL ? 2 * kt : 0, a.N / TILE);
+    it.init(nullptr, 0, CAUSAL ? 2 * kt : 0, kt * 128 >= len ? 0 : min(a.N / TILE, (len + TILE - 1) / TILE));
   TrOffsets<D> tro;
   tro.init();
   TileStage<T, D, NT> qs, gs;
@@ -190,6 +194,13 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
       }
       Kw[p2][pair][lane] = mine;
       keep_from_word(mine, keep_from);
+    }
+    if (kw0 + 32 > len) {   // this wavefront holds padded keys: their logits become -inf, hence P = 0
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+          if (kj >= len) sd[qb][i] = -INFINITY;
     }
     T8 pf[4], pfull[4];
 #pragma unroll
@@ -304,10 +315,13 @@ __global__ __launch_bounds__(64) void sparse_prep_kernel(const KArgs a) {
   const int bh = item / n_kt, kt = item % n_kt;
   const int h = bh % a.H;
   const uint8_t* col = a.mask + (int64_t)h * a.mask_sh + kt;
+  const int len = a.klen ? min(max(a.klen[bh / a.H], 0), a.N) : a.N;
+  const int first = a.causal ? kt : 0;                                     // same row range as the
+  const int limit = kt * 128 >= len ? 0 : min(a.T, (len + 127) / 128);     // tile iterator of dkv_rs_kernel
   int cnt = 0;
-  for (int base = a.causal ? kt : 0; base < a.T; base += 64) {
+  for (int base = first; base < limit; base += 64) {
     const int blk = base + (int)threadIdx.x;
-    const bool on = blk < a.T && blk >= (a.causal ? kt : 0) && col[(int64_t)blk * a.T] != 0;
+    const bool on = blk < limit && col[(int64_t)blk * a.T] != 0;
     cnt += __builtin_popcountll(__ballot(on));
   }
   if (threadIdx.x == 0) a.colcnt[item] = cnt;

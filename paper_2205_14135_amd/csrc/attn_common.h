@@ -30,6 +30,7 @@ struct KArgs {
   int causal;              // causal flag for the kernels that are not specialised on it
   const uint8_t* mask;     // block mask [T,T] (per head if mask_sh != 0) or nullptr
   int64_t mask_sh;
+  const int* klen;         // key-padding lengths [B] or nullptr
   int64_t sb, sh, sn;      // element strides of the [B,H,N,d] tensors
   int B, H, N, T;          // T = N / 128
   float tau;               // softmax scale

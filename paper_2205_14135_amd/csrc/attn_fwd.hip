@@ -79,11 +79,14 @@ __global__ __launch_bounds__(NT, 2) void fwd_kernel(const KArgs a) {
   float m_run = -INFINITY;  // running max of the scaled logits, base-2 domain
   float l_run = 0.f;        // this lane's share of the running row sum
 
+  // key-padding mask: keys >= len are masked, rows >= len produce O = 0, LSE = -inf
+  const int len = a.klen ? min(max(a.klen[b], 0), a.N) : a.N;
   TileIter<SPARSE> it;
   {
     int lim;
-    if constexpr (SPARSE) lim = CAUSAL ? qt + 1 : a.T;
-    else lim = CAUSAL ? 2 * qt + 2 : a.N / BC;
+    if constexpr (SPARSE) lim = min(CAUSAL ? qt + 1 : a.T, (len + 127) / 128);
+    else lim = min(CAUSAL ? 2 * qt + 2 : a.N / BC, (len + BC - 1) / BC);
+    if (qt * BR >= len) lim = 0;
     it.init(SPARSE ? a.mask + (int64_t)h * a.mask_sh + (int64_t)qt * a.T : nullptr, 1, 0, lim);
   }
 
@@ -137,14 +140,15 @@ __global__ __launch_bounds__(NT, 2) void fwd_kernel(const KArgs a) {
           s[kb] = mfma32(kf, qf[kk], s[kb]);
         }
       }
-      // ---- causal mask on tiles that cross the diagonal
-      if (CAUSAL && k0 + BC - 1 > q0) {
+      // ---- causal mask on tiles that cross the diagonal, padding mask on the last tile
+      if ((CAUSAL && k0 + BC - 1 > q0) || k0 + BC > len) {
+        const int last = CAUSAL ? min(qi, len - 1) : len - 1;   // last visible key of this row
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
           for (int i = 0; i < 16; ++i) {
             const int key = k0 + 32 * kb + 8 * (i >> 2) + 4 * g + (i & 3);
-            if (key > qi) s[kb][i] = -INFINITY;
+            if (key > last) s[kb][i] = -INFINITY;
           }
       }
       // ---- online softmax (base 2): row max, rescale factor, probabilities, row sum
@@ -211,7 +215,8 @@ __global__ __launch_bounds__(NT, 2) void fwd_kernel(const KArgs a) {
   }
 
   // ---- epilogue: normalise, apply the dropout scale, write O and L once
-  const float l_tot = l_run + xchg32(l_run);
+  const float l_sum = l_run + xchg32(l_run);
+  const float l_tot = qi < len ? l_sum : 0.f;   // padding rows: O = 0, LSE = -inf
   const float inv = l_tot > 0.f ? (DROPOUT ? a.keep_scale : 1.f) / l_tot : 0.f;
   if (g == 0) {
     const float lse = l_tot > 0.f ? (m_run + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f : -INFINITY;

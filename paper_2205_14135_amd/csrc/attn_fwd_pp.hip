@@ -66,8 +66,22 @@ __global__ __launch_bounds__(NT) void fwd_pp_kernel(const KArgs a) {
     for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
 
-  const int n_tiles = a.N / BC;
-  const int J = CAUSAL ? min(n_tiles, 4 * (qt + 1)) : n_tiles;
+  // key-padding mask: keys >= len are masked, rows >= len produce O = 0, LSE = -inf
+  const int len = a.klen ? min(max(a.klen[b], 0), a.N) : a.N;
+  const int n_tiles = min(a.N / BC, (len + BC - 1) / BC);
+  const int J = qt * BRW >= len ? 0 : (CAUSAL ? min(n_tiles, 4 * (qt + 1)) : n_tiles);
+  if (J == 0) {   // nothing visible for any row of this workgroup: write zeros and leave
+    if (valid) {
+      if (g == 0) a.LSE[(int64_t)bh * a.N + qi] = -INFINITY;
+      const int64_t o_off = head_off + (int64_t)qi * a.sn + (D / 2) * g;
+      if (a.o_fp32) {
+        for (int e = 0; e < D / 2; ++e) ((float*)a.O)[o_off + e] = 0.f;
+      } else {
+        for (int e = 0; e < D / 2; ++e) ((T*)a.O)[o_off + e] = (T)0.f;
+      }
+    }
+    return;
+  }
 
   const int lrow = tid / CPR, lchunk = tid % CPR;
   T8 kreg[NP], vreg[NP];
@@ -155,13 +169,14 @@ __global__ __launch_bounds__(NT) void fwd_pp_kernel(const KArgs a) {
 
   auto do_softmax = [&](int j) {
     const int k0 = j * BC;
-    if (CAUSAL && k0 + BC - 1 > q0) {
+    if ((CAUSAL && k0 + BC - 1 > q0) || k0 + BC > len) {   // diagonal tiles, and the padded last tile
+      const int last = CAUSAL ? min(qi, len - 1) : len - 1;
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
           const int key = k0 + 32 * kb + 8 * (i >> 2) + 4 * g + (i & 3);
-          if (key > qi) s[kb][i] = -INFINITY;
+          if (key > last) s[kb][i] = -INFINITY;
         }
     }
     float mx = s[0][0];
@@ -214,7 +229,7 @@ __global__ __launch_bounds__(NT) void fwd_pp_kernel(const KArgs a) {
   // ---- prologue: K(0) into LDS; K(1), V(0) into registers (J >= 2 always)
   gload_k(0);
   sstore_k(0);
-  gload_k(1);
+  if (1 < J) gload_k(1);
   gload_v(0);
   __syncthreads();
   if (group_b) { __builtin_amdgcn_sched_barrier(0); __syncthreads(); }   // B runs one block behind A
@@ -241,7 +256,8 @@ __global__ __launch_bounds__(NT) void fwd_pp_kernel(const KArgs a) {
   __syncthreads();   // every wavefront is done with the tiles: the buffers become output staging
 
   if (!valid) return;
-  const float l_tot = l_run + xchg32(l_run);
+  const float l_sum = l_run + xchg32(l_run);
+  const float l_tot = qi < len ? l_sum : 0.f;   // padding rows: O = 0, LSE = -inf
   const float inv = l_tot > 0.f ? (DROPOUT ? a.keep_scale : 1.f) / l_tot : 0.f;
   if (g == 0) {
     const float lse = l_tot > 0.f ? (m_run + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f : -INFINITY;

@@ -52,10 +52,11 @@ def _fwd(lib, p, ptr=0x1000):
 
 def test_struct_layout_matches_c():
     # int32 x5, pad, int64 x3, float, int32, float, pad, uint64 x2, int32, pad, pointer
-    assert ctypes.sizeof(binding.AttnParams) == 96
+    assert ctypes.sizeof(binding.AttnParams) == 104
     assert binding.AttnParams.stride_b.offset == 24
     assert binding.AttnParams.seed.offset == 64
     assert binding.AttnParams.stream.offset == 88
+    assert binding.AttnParams.key_lengths.offset == 96
 
 
 @pytest.mark.parametrize("kw,code", [
