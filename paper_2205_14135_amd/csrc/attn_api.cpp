@@ -74,11 +74,12 @@ void set_items(attn::KArgs& k, int tiles_per_head) {
   k.chunk = (k.n_items + attn::kXcds - 1) / attn::kXcds;
 }
 
-// Backward scratch layout: D vector | (block-sparse only) column counts | fp32 dK | fp32 dV.
+// Backward scratch layout: D vector, base-2 row statistic | (block-sparse only) column counts |
+// fp32 dK | fp32 dV.
 struct WsLayout { size_t d_bytes, cnt_bytes, acc_bytes; };
 WsLayout ws_layout(const attn_params* p) {
   WsLayout w;
-  w.d_bytes = align_up((size_t)p->B * p->H * p->N * sizeof(float), 256);
+  w.d_bytes = align_up(2 * (size_t)p->B * p->H * p->N * sizeof(float), 256);
   // column counts, then the segment list: one counter plus at most kMaxSegs entries per column
   w.cnt_bytes = align_up(((size_t)p->B * p->H * (p->N / attn::kMaskBlock) * (1 + attn::kMaxSegs) + 64) * sizeof(int), 256);
   w.acc_bytes = align_up((size_t)p->B * p->H * p->N * p->d * sizeof(float), 256);
@@ -111,6 +112,7 @@ int bwd_common(const attn_params* p, const uint8_t* mask, int64_t mask_sh, bool 
   c.k.Q = Q; c.k.K = K; c.k.V = V; c.k.O = const_cast<void*>(O); c.k.LSE = const_cast<float*>(LSE);
   c.k.dO = dO; c.k.dQ = dQ; c.k.dK = dK; c.k.dV = dV;
   c.k.Dvec = (float*)ws;
+  c.k.L2vec = c.k.Dvec + (size_t)p->B * p->H * p->N;
   if (sparse) {
     const WsLayout w = ws_layout(p);
     c.k.seglist = (int*)((char*)ws + w.d_bytes);
@@ -143,8 +145,8 @@ int attn_fwd(const attn_params* p, const void* Q, const void* K, const void* V, 
 size_t attn_bwd_workspace_bytes(const attn_params* p) {
   Checked c;
   if (check_params(p, &c) != ATTN_OK) return 0;
-  // D_i = rowsum(dO_i o O_i): one float per row
-  return align_up((size_t)p->B * p->H * p->N * sizeof(float), 256);
+  // D_i = rowsum(dO_i o O_i) and the base-2 row statistic: two floats per row
+  return ws_layout(p).d_bytes;
 }
 
 size_t attn_blocksparse_bwd_workspace_bytes(const attn_params* p) {

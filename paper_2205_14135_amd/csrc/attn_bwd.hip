@@ -7,7 +7,7 @@
 //     dV = P_dropped^T dO,  dP = (dO V^T) o Z,  dS = P o (dP - D),  dQ = tau dS K,  dK = tau dS^T Q.
 // The schedule differs from the paper's single K/V-outer loop with dQ read-modify-written in
 // HBM: three launches, none of which writes a partial result to HBM.
-//   1. rowdot_kernel : D = rowsum(dO o O)                               (HBM-bound, tiny)
+//   1. rowdot_kernel : D = rowsum(dO o O), L in base 2                  (HBM-bound, tiny)
 //   2. dq_kernel     : a workgroup owns 128 query rows and sweeps K/V tiles; dQ stays in
 //                      registers (S^T, dP^T layout: lane = query, like the forward kernel)
 //   3. dkv_kernel    : a workgroup owns 128 keys and sweeps Q/dO tiles; dK, dV stay in registers
@@ -26,7 +26,8 @@ constexpr int NT = 256;
 constexpr int TILE = 64;  // rows of the streamed tile (keys in dq_kernel, queries in dkv_kernel)
 
 // ---------------------------------------------------------------------------------------------
-// D_i = sum_d dO[i][d] * O[i][d]
+// D_i = sum_d dO[i][d] * O[i][d]; also the row statistic in the form the tile kernels use it:
+// L_i * log2(e), and +inf for a fully masked row (L_i = -inf) so that exp2(s - L) is 0 there.
 template <typename T, int D>
 __global__ __launch_bounds__(256) void rowdot_kernel(const KArgs a) {
   typedef typename Vec<T>::x8 T8;
@@ -54,7 +55,11 @@ __global__ __launch_bounds__(256) void rowdot_kernel(const KArgs a) {
   }
 #pragma unroll
   for (int s = CPR / 2; s >= 1; s >>= 1) acc += __shfl_xor(acc, s);
-  if (row < rows && ch == 0) a.Dvec[row] = acc;
+  if (row < rows && ch == 0) {
+    a.Dvec[row] = acc;
+    const float lse = a.LSE[row];
+    a.L2vec[row] = (lse == -INFINITY) ? INFINITY : lse * 1.4426950408889634f;
+  }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -112,7 +117,7 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const KArgs a) {
   TrOffsets<D> tro;
   tro.init();
   TileDma<T, D, NT / 64> dma;
-  dma.init(a.sn);
+  dma.init(a.sn, threadIdx.x >> 6);
 
   const float c = a.scale_log2;
   int jt = it.next();

@@ -13,7 +13,9 @@
 // leaves it (16-bit, in B's own register layout, plus the dropout keep bits) in LDS, and B runs
 // its dS / dK part one tile behind, so one workgroup barrier per tile orders everything.
 // LDS: Q tiles x3 (Q(j) is read by A in iteration j and by B in iteration j+1), dO tiles x2,
-// row statistics, P exchange x2.
+// row statistics, P exchange x2.  The Q / dO tile and the row statistics of tile j+1 arrive
+// during iteration j by asynchronous global-to-LDS copies: no staging registers, no LDS store
+// instructions, and a whole iteration for the data to land.
 #include "attn_common.h"
 #include "attn_tiles.h"
 
@@ -70,7 +72,7 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
   const int64_t head_off = (int64_t)b * a.sb + (int64_t)h * a.sh;
   const T* __restrict__ Qg = (const T*)a.Q + head_off;
   const T* __restrict__ Gg = (const T*)a.dO + head_off;
-  const float* __restrict__ Lg = a.LSE + (int64_t)bh * a.N;
+  const float* __restrict__ Lg = a.L2vec + (int64_t)bh * a.N;   // base 2, +inf for fully masked rows
   const float* __restrict__ Dg = a.Dvec + (int64_t)bh * a.N;
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -88,6 +90,9 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
     for (int kk = 0; kk < KK; ++kk)
       kvf[kk] = *(const T8*)(src + head_off + (int64_t)kj * a.sn + 16 * kk + 8 * g);
   }
+  // The fragments must have arrived before the tile loop: a wait for them inside the loop would
+  // also wait for the asynchronous tile copies in flight there.
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
   f32x16 acc[DB];  // role A: dV^T, role B: dK^T   (rows d, column = this lane's key)
 #pragma unroll
   for (int db = 0; db < DB; ++db)
@@ -106,21 +111,15 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
     it.init(nullptr, 0, CAUSAL ? 2 * kt : 0, kt * 128 >= len ? 0 : min(a.N / TILE, (len + TILE - 1) / TILE));
   TrOffsets<D> tro;
   tro.init();
-  TileStage<T, D, NT> qs, gs;
-  float lreg = 0.f, dreg = 0.f;
-  auto load_tile = [&](int t) {
-    qs.load(Qg, a.sn, t * TILE);
-    gs.load(Gg, a.sn, t * TILE);
-    if (threadIdx.x < TILE) {
-      const float lse = Lg[t * TILE + threadIdx.x];
-      lreg = (lse == -INFINITY) ? INFINITY : lse * 1.4426950408889634f;
-      dreg = Dg[t * TILE + threadIdx.x];
-    }
-  };
-  auto store_tile = [&](int q3, int p2) {
-    qs.store(Qs[q3]);
-    gs.store(Gs[p2]);
-    if (threadIdx.x < TILE) { Ls[p2][threadIdx.x] = lreg; Ds[q3][threadIdx.x] = dreg; }
+  TileAsync<T, D, NT / 64> dma;
+  dma.init(a.sn, wave);
+  // starts the copies of tile t into buffers (q3, p2); wait_async_copies() and a workgroup
+  // barrier must come before anyone reads them
+  auto fetch_tile = [&](int t, int q3, int p2) {
+    dma.copy(Qg + (int64_t)t * TILE * a.sn, Qs[q3]);
+    dma.copy(Gg + (int64_t)t * TILE * a.sn, Gs[p2]);
+    if (wave == 1) async_copy_b32(Lg + t * TILE + lane, __builtin_amdgcn_readfirstlane(lds_addr(Ls[p2])));
+    if (wave == 5) async_copy_b32(Dg + t * TILE + lane, __builtin_amdgcn_readfirstlane(lds_addr(Ds[q3])));
   };
 
   const float c = a.scale_log2;
@@ -255,19 +254,15 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
 
   // ---- pipeline over the tiles of this key block
   int t0 = it.next();
-  int t1 = t0 >= 0 ? it.next() : -1;
-  if (t0 >= 0) { load_tile(t0); store_tile(0, 0); }
-  if (t1 >= 0) load_tile(t1);
+  if (t0 >= 0) fetch_tile(t0, 0, 0);
   int q3 = 0, p2 = 0;          // buffer indices of the current tile: j % 3 and j % 2
   bool have_prev = false, prev_active = false;
   while (t0 >= 0) {
-    __syncthreads();
-    const int t2 = t1 >= 0 ? it.next() : -1;
+    wait_async_copies();       // this wavefront's share of tile t0 has landed ...
+    __syncthreads();           // ... and so has everyone else's; the buffers of tile t0 - 2 are free
+    const int t1 = it.next();
     const int q3n = q3 == 2 ? 0 : q3 + 1;
-    if (t1 >= 0) {
-      store_tile(q3n, p2 ^ 1);
-      if (t2 >= 0) load_tile(t2);
-    }
+    if (t1 >= 0) fetch_tile(t1, q3n, p2 ^ 1);
     const int i0 = t0 * TILE;
     const bool active = !CAUSAL || i0 + TILE - 1 >= kw0;
     if (!role_b) {
@@ -279,7 +274,6 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
     have_prev = true;
     prev_active = active;
     t0 = t1;
-    t1 = t2;
     q3 = q3n;
     p2 ^= 1;
   }

@@ -9,11 +9,14 @@
 // workgroup's 256 query rows, and workgroup barriers keep group B exactly one block behind
 // group A: while one group issues MFMA the other issues the softmax VALU work.
 //
-// K and V tiles are double buffered in LDS and shared by both groups.  In global slot numbers
-// (slot 2j: A in M(j), B in X(j-1); slot 2j+1: A in X(j), B in M(j)) K(t) is read in slots
-// 2t, 2t+1 and V(t) in slots 2t+2, 2t+3, so K(t) may be written in slots 2t-2, 2t-1 and V(t) in
-// slots 2t, 2t+1.  Every wavefront stages 1/8 of each tile (global -> registers -> LDS): it stores
-// its share of K(j+1) and V(j) at the start of its own M(j), inside both windows for either group.
+// K and V tiles are double buffered in LDS (unpadded, XOR-swizzled) and shared by both groups.
+// In global slot numbers (slot 2j: A in M(j), B in X(j-1); slot 2j+1: A in X(j), B in M(j)) K(t)
+// is read in slots 2t, 2t+1 and V(t) in slots 2t+2, 2t+3, so K(t) may be written in slots 2t-2,
+// 2t-1 and V(t) in slots 2t, 2t+1.  Tiles arrive by asynchronous global-to-LDS copies issued from
+// the vector blocks, which use no LDS themselves: group A copies K(j+1) at the start of its X(j)
+// (slot 2j+1) and group B copies V(j+1) at the start of its X(j) (slot 2j+2); the barrier that
+// closes the block waits for the copies, so they are visible from the next slot on.  The matrix
+// blocks carry no staging work at all.
 #include "attn_common.h"
 #include "attn_tiles.h"
 
@@ -28,12 +31,10 @@ template <typename T, int D, bool CAUSAL, bool DROPOUT>
 __global__ __launch_bounds__(NT) void fwd_pp_kernel(const KArgs a) {
   typedef typename Vec<T>::x8 T8;
   typedef typename Vec<T>::x4 T4;
-  constexpr int KS = D + 8, VS = D + 32;  // padded row strides, as in fwd_kernel
   constexpr int KK = D / 16, DB = D / 32;
-  constexpr int CPR = D / 8, RPP = NT / CPR, NP = BC / RPP;
 
-  __shared__ __attribute__((aligned(16))) T Ks[2][BC * KS];
-  __shared__ __attribute__((aligned(16))) T Vs[2][BC * VS];
+  __shared__ __attribute__((aligned(16))) T Ks[2][BC * D];
+  __shared__ __attribute__((aligned(16))) T Vs[2][BC * D];
 
   const int item = xcd_item(a.n_items, a.chunk);
   if (item < 0) return;
@@ -83,29 +84,10 @@ __global__ __launch_bounds__(NT) void fwd_pp_kernel(const KArgs a) {
     return;
   }
 
-  const int lrow = tid / CPR, lchunk = tid % CPR;
-  T8 kreg[NP], vreg[NP];
-  const T* const k_thr = Kg + (int64_t)lrow * a.sn + 8 * lchunk;   // per-thread base; tile offsets are uniform
-  const T* const v_thr = Vg + (int64_t)lrow * a.sn + 8 * lchunk;
-  auto gload_k = [&](int jt) {
-#pragma unroll
-    for (int p = 0; p < NP; ++p) kreg[p] = *(const T8*)(k_thr + (int64_t)(jt * BC + p * RPP) * a.sn);
-  };
-  auto gload_v = [&](int jt) {
-#pragma unroll
-    for (int p = 0; p < NP; ++p) vreg[p] = *(const T8*)(v_thr + (int64_t)(jt * BC + p * RPP) * a.sn);
-  };
-  auto sstore_k = [&](int buf) {
-#pragma unroll
-    for (int p = 0; p < NP; ++p) *(T8*)(&Ks[buf][(p * RPP + lrow) * KS + 8 * lchunk]) = kreg[p];
-  };
-  auto sstore_v = [&](int buf) {
-#pragma unroll
-    for (int p = 0; p < NP; ++p) *(T8*)(&Vs[buf][(p * RPP + lrow) * VS + 8 * lchunk]) = vreg[p];
-  };
-
-  const int i16 = lane & 15, q16 = lane >> 4;
-  const int v_lane_off = (4 * g + (i16 >> 2)) * VS + 16 * (q16 & 1) + 4 * (i16 & 3);
+  TileDma<T, D, 4> dma;   // the four wavefronts of a group copy a whole tile
+  dma.init(a.sn, wave & 3);
+  TrOffsets<D> tro;
+  tro.init();
   const float c = a.scale_log2;
 
   f32x16 s[2];
@@ -117,14 +99,11 @@ __global__ __launch_bounds__(NT) void fwd_pp_kernel(const KArgs a) {
   // matrix pipe does not idle on LDS latency.
   constexpr int PF = 4;
   auto k_frag = [&](const T* kbuf, int f) {  // f = 2 * kk + kb
-    return *(const T8*)(kbuf + (32 * (f & 1) + r) * KS + 16 * (f >> 1) + 8 * g);
+    return *(const T8*)(kbuf + lds_off<D>(32 * (f & 1) + r, 2 * (f >> 1) + g));
   };
   auto v_frag = [&](const T* vbuf, int f) {  // f = DB * cc + db: consecutive MFMAs hit different accumulators
-    const T* vp = vbuf + v_lane_off + (16 * (f / DB)) * VS + 32 * (f % DB);
-    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vp));
-    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vp + 8 * VS));
-    const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-    return __builtin_bit_cast(T8, both);
+    const T* base = vbuf + 16 * (f / DB) * D;
+    return tr_frag<T8>(base + tro.off[f % DB][0], base + tro.off[f % DB][1]);
   };
 
   // M block: O^T += V(jv)^T P^T (if do_pv) followed by S^T = K(js) Q^T (if do_s), as one
@@ -226,28 +205,29 @@ __global__ __launch_bounds__(NT) void fwd_pp_kernel(const KArgs a) {
       for (int t = 0; t < 8; ++t) pf[cc][t] = (T)s[cc >> 1][8 * (cc & 1) + t];
   };
 
-  // ---- prologue: K(0) into LDS; K(1), V(0) into registers (J >= 2 always)
-  gload_k(0);
-  sstore_k(0);
-  if (1 < J) gload_k(1);
-  gload_v(0);
+  // ---- prologue: A copies K(0); B, which starts one block later, copies V(0) in slot 0
+  if (!group_b) dma.copy(Kg, Ks[0]);
   __syncthreads();
-  if (group_b) { __builtin_amdgcn_sched_barrier(0); __syncthreads(); }   // B runs one block behind A
+  if (group_b) {
+    dma.copy(Vg, Vs[0]);
+    __builtin_amdgcn_sched_barrier(0);
+    __syncthreads();   // B runs one block behind A
+  }
 
   for (int j = 0; j < J; ++j) {
-    // ---- M(j): publish this wavefront's share of K(j+1) and V(j), fetch the next tiles, matrix work
-    if (j + 1 < J) sstore_k((j + 1) & 1);
-    sstore_v(j & 1);
-    if (j + 2 < J) gload_k(j + 2);
-    if (j + 1 < J) gload_v(j + 1);
+    // ---- M(j): matrix work only
     do_M(j > 0 && active(j - 1), j - 1, active(j), j);
     __builtin_amdgcn_sched_barrier(0);
     __syncthreads();
     __builtin_amdgcn_sched_barrier(0);
-    // ---- X(j): online softmax
+    // ---- X(j): start the copy of the next tile, then the online softmax
+    if (j + 1 < J) {
+      if (!group_b) dma.copy(Kg + (int64_t)(j + 1) * BC * a.sn, Ks[(j + 1) & 1]);
+      else dma.copy(Vg + (int64_t)(j + 1) * BC * a.sn, Vs[(j + 1) & 1]);
+    }
     if (active(j)) do_softmax(j);
     __builtin_amdgcn_sched_barrier(0);
-    __syncthreads();
+    __syncthreads();   // also waits for this wavefront's copies
     __builtin_amdgcn_sched_barrier(0);
   }
   do_M(active(J - 1), J - 1, false, 0);

@@ -86,7 +86,7 @@ def test_null_pointers_and_workspace(lib):
     assert _fwd(lib, p, ptr=0) == -1
     v, z = ctypes.c_void_p(0x1000), ctypes.c_void_p(0)
     need = lib.attn_bwd_workspace_bytes(ctypes.byref(p))
-    assert need == 512 and need % 256 == 0
+    assert need == 1024 and need % 256 == 0
     args = [v] * 9
     assert lib.attn_bwd(ctypes.byref(p), *args, z, need) == -7                      # NULL workspace
     assert lib.attn_bwd(ctypes.byref(p), *args, ctypes.c_void_p(0x1010), need) == -7  # misaligned
@@ -94,7 +94,7 @@ def test_null_pointers_and_workspace(lib):
     assert lib.attn_bwd(ctypes.byref(p), *([v] * 8 + [z]), v, need) == -1
     assert lib.attn_bwd_workspace_bytes(ctypes.byref(_params(d=7))) == 0
     sparse_need = lib.attn_blocksparse_bwd_workspace_bytes(ctypes.byref(p))
-    assert sparse_need == 512 + 512 + 2 * 128 * 64 * 4          # D | segment list + column counts | fp32 dK, dV
+    assert sparse_need == 1024 + 512 + 2 * 128 * 64 * 4         # D, L | segment list + column counts | fp32 dK, dV
     assert lib.attn_blocksparse_bwd_workspace_bytes(ctypes.byref(_params(N=100))) == 0
     args_m = [v, 128, 0] + [v] * 9
     assert lib.attn_blocksparse_bwd(ctypes.byref(p), *args_m, v, need) == -7     # dense size is too small
