@@ -37,6 +37,7 @@ int check_params(const attn_params* p, Checked* out) {
   }
   // rows must start on 16-byte boundaries for the vector loads
   if (sn < p->d || sn % 8 != 0 || sh % 8 != 0 || sb % 8 != 0 || sh < 0 || sb < 0) return ATTN_ERR_SHAPE;
+  if (sn > ((int64_t)1 << 23)) return ATTN_ERR_SHAPE;   // the tile copies address 64 rows with 32-bit byte offsets
   if (!(p->dropout_p >= 0.0f && p->dropout_p < 1.0f)) return ATTN_ERR_DROPOUT_P;
   if (!std::isfinite(p->softmax_scale) || !(p->softmax_scale > 0.0f)) return ATTN_ERR_SCALE;
 

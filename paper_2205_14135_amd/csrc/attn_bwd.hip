@@ -116,7 +116,7 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const KArgs a) {
   }
   TrOffsets<D> tro;
   tro.init();
-  TileDma<T, D, NT / 64> dma;
+  TileAsync<T, D, NT / 64> dma;
   dma.init(a.sn, threadIdx.x >> 6);
 
   const float c = a.scale_log2;
@@ -126,7 +126,8 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const KArgs a) {
     dma.copy(Kg + (int64_t)jt * TILE * a.sn, Ks[0]);
     dma.copy(Vg + (int64_t)jt * TILE * a.sn, Vs[0]);
   }
-  __syncthreads();   // tile 0 has landed (the compiler waits for the copies before the barrier)
+  wait_async_copies();
+  __syncthreads();   // tile 0 has landed, and so have the Q / dO fragments
   while (jt >= 0) {
     const int jn = it.next();
     if (jn >= 0) {   // next tile streams into the other buffer while this one is used
@@ -143,14 +144,28 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const KArgs a) {
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) { s[kb][i] = 0.f; dp[kb][i] = 0.f; }
+      // S^T = K Q^T and dP^T = V dO^T as one stream of 4 KK MFMAs; operand reads run PF fragments
+      // ahead of their MFMA (the scheduling barriers keep that distance)
+      constexpr int PF = 4;
+      auto kv_frag = [&](int f) {   // f = 4 kk + 2 kb + (0: K, 1: V)
+        const int off = lds_off<D>(32 * ((f >> 1) & 1) + r, 2 * (f >> 2) + g);
+        return *(const T8*)(((f & 1) ? Vt : Kt) + off);
+      };
+      {
+        T8 ring[PF];
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk)
+        for (int f = 0; f < PF; ++f) ring[f] = kv_frag(f);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-          const int off = lds_off<D>(32 * kb + r, 2 * kk + g);
-          s[kb] = mfma32(*(const T8*)(Kt + off), qf[kk], s[kb]);     // S^T  = K Q^T
-          dp[kb] = mfma32(*(const T8*)(Vt + off), gf[kk], dp[kb]);   // dP^T = V dO^T
+        for (int f = 0; f < 4 * KK; ++f) {
+          const T8 cur = ring[f % PF];
+          const int kk = f >> 2, kb = (f >> 1) & 1;
+          if (f & 1) dp[kb] = mfma32(cur, gf[kk], dp[kb]);
+          else s[kb] = mfma32(cur, qf[kk], s[kb]);
+          if (f + PF < 4 * KK) ring[f % PF] = kv_frag(f + PF);
+          __builtin_amdgcn_sched_barrier(0);
         }
+      }
       if (k0 + TILE > len) {   // the tile holds padded keys: their logits become -inf, hence P = 0
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
@@ -184,14 +199,25 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const KArgs a) {
 #pragma unroll
         for (int t = 0; t < 8; ++t) dsf[cc][t] = (T)s[cc >> 1][8 * (cc & 1) + t];
       // dQ^T += K^T dS^T
+      auto kt_frag = [&](int f) {   // f = DB cc + db: consecutive MFMAs hit different accumulators
+        const T* base = Kt + 16 * (f / DB) * D;
+        return tr_frag<T8>(base + tro.off[f % DB][0], base + tro.off[f % DB][1]);
+      };
+      {
+        T8 ring[PF];
 #pragma unroll
-      for (int db = 0; db < DB; ++db)
+        for (int f = 0; f < PF; ++f) ring[f] = kt_frag(f);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int cc = 0; cc < 4; ++cc) {
-          const T* base = Kt + 16 * cc * D;
-          dq[db] = mfma32(tr_frag<T8>(base + tro.off[db][0], base + tro.off[db][1]), dsf[cc], dq[db]);
+        for (int f = 0; f < 4 * DB; ++f) {
+          const T8 cur = ring[f % PF];
+          dq[f % DB] = mfma32(cur, dsf[f / DB], dq[f % DB]);
+          if (f + PF < 4 * DB) ring[f % PF] = kt_frag(f + PF);
+          __builtin_amdgcn_sched_barrier(0);
         }
+      }
     }
+    wait_async_copies();
     __syncthreads();   // next tile has landed, and everyone is done with this buffer
     jt = jn;
     buf ^= 1;

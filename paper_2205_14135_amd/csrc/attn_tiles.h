@@ -69,6 +69,16 @@ __device__ __forceinline__ void async_copy_b128(const void* gptr_lane, uint32_t 
   (void)gptr_lane; (void)lds_byte_addr;
 #endif
 }
+// Same with the address split into a wavefront-uniform base (scalar registers) and a per-lane
+// byte offset: no vector ALU work when only the base changes from tile to tile.
+__device__ __forceinline__ void async_copy_b128(const void* gbase_uniform, uint32_t byte_off_lane, uint32_t lds_byte_addr) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :: "s"(lds_byte_addr), "v"(byte_off_lane), "s"(gbase_uniform) : "memory");
+#else
+  (void)gbase_uniform; (void)byte_off_lane; (void)lds_byte_addr;
+#endif
+}
 __device__ __forceinline__ void async_copy_b32(const void* gptr_lane, uint32_t lds_byte_addr) {
 #if defined(__HIP_DEVICE_COMPILE__)
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off"
@@ -77,9 +87,12 @@ __device__ __forceinline__ void async_copy_b32(const void* gptr_lane, uint32_t l
   (void)gptr_lane; (void)lds_byte_addr;
 #endif
 }
+// vmcnt(0), as an instruction the compiler sees: it then also knows that its own earlier loads
+// have completed and places no second wait for them where copies are in flight.
 __device__ __forceinline__ void wait_async_copies() {
 #if defined(__HIP_DEVICE_COMPILE__)
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(0x0F70);
+  asm volatile("" ::: "memory");
 #endif
 }
 __device__ __forceinline__ uint32_t lds_addr(const void* p) {
@@ -90,21 +103,22 @@ __device__ __forceinline__ uint32_t lds_addr(const void* p) {
 template <typename T, int D, int NW> struct TileAsync {
   static constexpr int CPR = D / 8, RPC = 64 / CPR, NCOPY = D / 8, PER_WAVE = NCOPY / NW;
   static_assert(NCOPY % NW == 0, "copies must divide evenly over the wavefronts");
-  int64_t goff[PER_WAVE];
-  int wave;
+  uint32_t goff[PER_WAVE];   // byte offset of this lane's chunk inside a tile whose row 0 is at 0
+  int wave;                  // (the host checks that 64 rows of the tensor span less than 2^31 bytes)
   __device__ __forceinline__ void init(int64_t sn, int wave_index) {
     const int lane = threadIdx.x & 63;
     wave = wave_index;
 #pragma unroll
     for (int p = 0; p < PER_WAVE; ++p) {
       const int row = (wave * PER_WAVE + p) * RPC + lane / CPR;
-      goff[p] = (int64_t)row * sn + 8 * ((lane % CPR) ^ swz_bits<D>(row));
+      goff[p] = (uint32_t)(((int64_t)row * sn + 8 * ((lane % CPR) ^ swz_bits<D>(row))) * (int64_t)sizeof(T));
     }
   }
+  // g_row0 must be wavefront-uniform
   __device__ __forceinline__ void copy(const T* g_row0, const T* lds_tile) const {
     const uint32_t base = __builtin_amdgcn_readfirstlane(lds_addr(lds_tile) + (wave * PER_WAVE) * 1024);
 #pragma unroll
-    for (int p = 0; p < PER_WAVE; ++p) async_copy_b128(g_row0 + goff[p], base + p * 1024);
+    for (int p = 0; p < PER_WAVE; ++p) async_copy_b128(g_row0, goff[p], base + p * 1024);
   }
 };
 
