@@ -26,7 +26,8 @@ constexpr int NT = 256;
 constexpr int TILE = 64;  // rows of the streamed tile (keys in dq_kernel, queries in dkv_kernel)
 
 // ---------------------------------------------------------------------------------------------
-// D_i = sum_d dO[i][d] * O[i][d]; also the row statistic in the form the tile kernels use it:
+// -D_i = -sum_d dO[i][d] * O[i][d] (stored negated: the tile kernels start the dP accumulators
+// from it, so that dP - D needs no instruction of its own); also the row statistic in the form the tile kernels use it:
 // L_i * log2(e), and +inf for a fully masked row (L_i = -inf) so that exp2(s - L) is 0 there.
 template <typename T, int D>
 __global__ __launch_bounds__(256) void rowdot_kernel(const KArgs a) {
@@ -56,7 +57,7 @@ __global__ __launch_bounds__(256) void rowdot_kernel(const KArgs a) {
 #pragma unroll
   for (int s = CPR / 2; s >= 1; s >>= 1) acc += __shfl_xor(acc, s);
   if (row < rows && ch == 0) {
-    a.Dvec[row] = acc;
+    a.Dvec[row] = -acc;
     const float lse = a.LSE[row];
     a.L2vec[row] = (lse == -INFINITY) ? INFINITY : lse * 1.4426950408889634f;
   }
@@ -96,7 +97,7 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const KArgs a) {
   const float lse = a.LSE[(int64_t)bh * a.N + qi];
   // base-2 statistic; a row that saw no key has P = 0 everywhere
   const float l2 = (lse == -INFINITY) ? INFINITY : lse * 1.4426950408889634f;
-  const float dsum = a.Dvec[(int64_t)bh * a.N + qi];
+  const float neg_d = a.Dvec[(int64_t)bh * a.N + qi];   // -D_i
 
   f32x16 dq[DB];
 #pragma unroll
@@ -143,7 +144,12 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const KArgs a) {
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) { s[kb][i] = 0.f; dp[kb][i] = 0.f; }
+        for (int i = 0; i < 16; ++i) {
+          s[kb][i] = 0.f;
+          // every accumulator element of a lane belongs to the lane's query: without dropout the
+          // product starts from -D_i and ends as dP - D
+          dp[kb][i] = DROPOUT ? 0.f : neg_d;
+        }
       // S^T = K Q^T and dP^T = V dO^T as one stream of 4 KK MFMAs; operand reads run PF fragments
       // ahead of their MFMA (the scheduling barriers keep that distance)
       constexpr int PF = 4;
@@ -189,8 +195,8 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const KArgs a) {
             float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][i], c, -l2));
             if (CAUSAL && k0 + 32 * kb + 8 * i4 + 4 * g + e > qi) p = 0.f;
             float dpv = dp[kb][i];
-            if constexpr (DROPOUT) dpv = (w[e] >= a.drop_thr) ? dpv * a.keep_scale : 0.f;
-            s[kb][i] = p * (dpv - dsum);
+            if constexpr (DROPOUT) dpv = ((w[e] >= a.drop_thr) ? dpv * a.keep_scale : 0.f) + neg_d;
+            s[kb][i] = p * dpv;
           }
         }
       T8 dsf[4];
@@ -236,7 +242,7 @@ __global__ __launch_bounds__(NT, 1) void dkv_kernel(const KArgs a) {
   __shared__ __attribute__((aligned(16))) T Qs[TILE * D];
   __shared__ __attribute__((aligned(16))) T Gs[TILE * D];   // dO tile
   __shared__ __attribute__((aligned(16))) float Ls[TILE];   // base-2 row statistic
-  __shared__ __attribute__((aligned(16))) float Ds[TILE];   // D_i
+  __shared__ __attribute__((aligned(16))) float Ds[TILE];   // -D_i
 
   const int item = xcd_item(a.n_items, a.chunk);
   if (item < 0) return;
@@ -351,7 +357,7 @@ __global__ __launch_bounds__(NT, 1) void dkv_kernel(const KArgs a) {
               pk = keep ? p : 0.f;
             }
             pd[qb][i] = pk;
-            s[qb][i] = p * (dpv - d4[e]);
+            s[qb][i] = p * (dpv + d4[e]);   // the scratch vector holds -D
           }
         }
       T8 pf[4], dsf[4];

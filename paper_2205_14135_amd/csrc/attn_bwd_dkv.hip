@@ -33,7 +33,7 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
   __shared__ __attribute__((aligned(16))) T Qs[3][TILE * D];
   __shared__ __attribute__((aligned(16))) T Gs[2][TILE * D];      // dO tiles
   __shared__ __attribute__((aligned(16))) float Ls[2][TILE];      // base-2 row statistic
-  __shared__ __attribute__((aligned(16))) float Ds[3][TILE];      // D_i
+  __shared__ __attribute__((aligned(16))) float Ds[3][TILE];      // -D_i
   __shared__ __attribute__((aligned(16))) T8 Px[2][4][4][64];     // P exchange [buf][pair][chunk][lane]
   __shared__ uint32_t Kw[2][4][64];                                // dropout keep words [buf][pair][lane]
 
@@ -129,7 +129,8 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
   // for LDS latency on every instruction.
   constexpr int PF = 4;
   // product of a row-read tile with the register fragments: sd[qb] = Tile[32 qb .. +31][:] . kvf
-  auto row_product = [&](const T* tile) {
+  // cinit: 64 per-row start values of the accumulator (nullptr: zero)
+  auto row_product = [&](const T* tile, const float* cinit) {
     auto frag = [&](int f) { return *(const T8*)(tile + lds_off<D>(32 * (f & 1) + r, 2 * (f >> 1) + g)); };  // f = 2 kk + qb
     T8 ring[PF];
 #pragma unroll
@@ -140,8 +141,17 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
       const T8 cur = ring[f % PF];
       if (f < 2) {
         f32x16 z;
+        if (cinit != nullptr) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) z[i] = 0.f;
+          for (int i4 = 0; i4 < 4; ++i4) {
+            const f32x4 c4 = *(const f32x4*)(cinit + 32 * f + 8 * i4 + 4 * g);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) z[4 * i4 + e] = c4[e];
+          }
+        } else {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) z[i] = 0.f;
+        }
         sd[f & 1] = mfma32(cur, kvf[f >> 1], z);
       } else {
         sd[f & 1] = mfma32(cur, kvf[f >> 1], sd[f & 1]);
@@ -178,7 +188,7 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
 
   // ---- role A, tile with first query i0, buffers (q3, p2)
   auto role_a = [&](int i0, int q3, int p2) {
-    row_product(Qs[q3]);                                   // S = Q K^T
+    row_product(Qs[q3], nullptr);                          // S = Q K^T
     uint32_t keep_from[4] = {0, 0, 0, 0};
     if constexpr (DROPOUT) {
       // a lane draws for query (r % 4) of each group of four consecutive queries; the four
@@ -236,17 +246,18 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
     for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
       for (int i4 = 0; i4 < 4; ++i4) {
-        const f32x4 d4 = *(const f32x4*)(&Ds[q3][32 * qb + 8 * i4 + 4 * g]);
+        f32x4 d4 = {0.f, 0.f, 0.f, 0.f};
+        if constexpr (DROPOUT) d4 = *(const f32x4*)(&Ds[q3][32 * qb + 8 * i4 + 4 * g]);   // -D_i
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int i = 4 * i4 + e;
           const int cc = 2 * qb + (i4 >> 1), t = 4 * (i4 & 1) + e;
-          float dpv = sd[qb][i];
+          float dpv = sd[qb][i];   // without dropout: already dP - D
           if constexpr (DROPOUT) {
             const bool keep = (keep_from[e] >> (4 * (4 * qb + i4))) & 1u;
-            dpv = keep ? dpv * a.keep_scale : 0.f;
+            dpv = (keep ? dpv * a.keep_scale : 0.f) + d4[e];
           }
-          dsf[cc][t] = (T)((float)pin[cc][t] * (dpv - d4[e]));
+          dsf[cc][t] = (T)((float)pin[cc][t] * dpv);
         }
       }
     col_product(Qs[q3], dsf);                               // dK^T += Q^T dS
@@ -269,7 +280,8 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
       if (active) role_a(i0, q3, p2);
     } else {
       if (have_prev && prev_active) role_b_ds_dk(q3 == 0 ? 2 : q3 - 1, p2 ^ 1);
-      if (active) row_product(Gs[p2]);                     // dP = dO V^T
+      // dP = dO V^T; without dropout it starts from -D, so the result is dP - D
+      if (active) row_product(Gs[p2], DROPOUT ? nullptr : Ds[q3]);
     }
     have_prev = true;
     prev_active = active;

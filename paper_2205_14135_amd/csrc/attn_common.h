@@ -22,7 +22,7 @@ struct KArgs {
   float* LSE;              // fwd: out; bwd: in        [B,H,N]
   const void* dO;          // bwd in
   void* dQ; void* dK; void* dV;   // bwd out
-  float* Dvec;             // bwd scratch: D_i = rowsum(dO_i o O_i)   [B,H,N]
+  float* Dvec;             // bwd scratch: -D_i = -rowsum(dO_i o O_i)   [B,H,N]
   float* L2vec;            // bwd scratch: L_i * log2(e), +inf where L_i = -inf   [B,H,N]
   int* colcnt;             // block-sparse bwd scratch: kept blocks per mask column   [B*H, T]
   int* seglist;            // block-sparse bwd scratch: [0] = number of entries, then (column * kMaxSegs + segment)
