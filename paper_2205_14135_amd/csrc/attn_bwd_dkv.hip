@@ -12,10 +12,13 @@
 // instruction streams on a SIMD overlap MFMA with the exp / dS VALU work.  B needs A's P: A
 // leaves it (16-bit, in B's own register layout, plus the dropout keep bits) in LDS, and B runs
 // its dS / dK part one tile behind, so one workgroup barrier per tile orders everything.
-// LDS: Q tiles x3 (Q(j) is read by A in iteration j and by B in iteration j+1), dO tiles x2,
-// row statistics, P exchange x2.  The Q / dO tile and the row statistics of tile j+1 arrive
-// during iteration j by asynchronous global-to-LDS copies: no staging registers, no LDS store
-// instructions, and a whole iteration for the data to land.
+// Tiles arrive by asynchronous global-to-LDS copies (no staging registers, no LDS store
+// instructions).  Issuing a tile's 34 copies stalls a wavefront for hundreds of clocks (the
+// vector memory path of a compute unit takes 64 bytes per clock), so only the role A wavefronts
+// issue them, at the END of their iteration, where they would otherwise idle waiting for role B,
+// and for the tile two iterations ahead, so the data has a full iteration to land.
+// LDS: Q and D x4 (tile j is read by A in iteration j and by B in iteration j+1, tile j+2 is
+// being written), dO and L x3, P exchange x2.
 #include "attn_common.h"
 #include "attn_tiles.h"
 
@@ -30,10 +33,10 @@ template <typename T, int D, bool CAUSAL, bool DROPOUT, bool SPARSE>
 __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
   typedef typename Vec<T>::x8 T8;
   constexpr int KK = D / 16, DB = D / 32;
-  __shared__ __attribute__((aligned(16))) T Qs[3][TILE * D];
-  __shared__ __attribute__((aligned(16))) T Gs[2][TILE * D];      // dO tiles
-  __shared__ __attribute__((aligned(16))) float Ls[2][TILE];      // base-2 row statistic
-  __shared__ __attribute__((aligned(16))) float Ds[3][TILE];      // -D_i
+  __shared__ __attribute__((aligned(16))) T Qs[4][TILE * D];
+  __shared__ __attribute__((aligned(16))) T Gs[3][TILE * D];      // dO tiles
+  __shared__ __attribute__((aligned(16))) float Ls[3][TILE];      // base-2 row statistic
+  __shared__ __attribute__((aligned(16))) float Ds[4][TILE];      // -D_i
   __shared__ __attribute__((aligned(16))) T8 Px[2][4][4][64];     // P exchange [buf][pair][chunk][lane]
   __shared__ uint32_t Kw[2][4][64];                                // dropout keep words [buf][pair][lane]
 
@@ -111,15 +114,16 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
     it.init(nullptr, 0, CAUSAL ? 2 * kt : 0, kt * 128 >= len ? 0 : min(a.N / TILE, (len + TILE - 1) / TILE));
   TrOffsets<D> tro;
   tro.init();
-  TileAsync<T, D, NT / 64> dma;
-  dma.init(a.sn, wave);
-  // starts the copies of tile t into buffers (q3, p2); wait_async_copies() and a workgroup
-  // barrier must come before anyone reads them
-  auto fetch_tile = [&](int t, int q3, int p2) {
-    dma.copy(Qg + (int64_t)t * TILE * a.sn, Qs[q3]);
-    dma.copy(Gg + (int64_t)t * TILE * a.sn, Gs[p2]);
-    if (wave == 1) async_copy_b32(Lg + t * TILE + lane, __builtin_amdgcn_readfirstlane(lds_addr(Ls[p2])));
-    if (wave == 5) async_copy_b32(Dg + t * TILE + lane, __builtin_amdgcn_readfirstlane(lds_addr(Ds[q3])));
+  TileAsync<T, D, 4> dma;   // the four role A wavefronts copy whole tiles
+  dma.init(a.sn, wave & 3);
+  // copies per tile issued by this wavefront (role A only): Q and dO shares, plus L (wave 1) or D (wave 2)
+  constexpr int kTileCopies = 2 * TileAsync<T, D, 4>::PER_WAVE;
+  // starts the copies of tile t into ring slots (q4, g3)
+  auto fetch_tile = [&](int t, int q4, int g3) {
+    dma.copy(Qg + (int64_t)t * TILE * a.sn, Qs[q4]);
+    dma.copy(Gg + (int64_t)t * TILE * a.sn, Gs[g3]);
+    if (wave == 1) async_copy_b32(Lg + t * TILE + lane, __builtin_amdgcn_readfirstlane(lds_addr(Ls[g3])));
+    if (wave == 2) async_copy_b32(Dg + t * TILE + lane, __builtin_amdgcn_readfirstlane(lds_addr(Ds[q4])));
   };
 
   const float c = a.scale_log2;
@@ -187,8 +191,8 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
   };
 
   // ---- role A, tile with first query i0, buffers (q3, p2)
-  auto role_a = [&](int i0, int q3, int p2) {
-    row_product(Qs[q3], nullptr);                          // S = Q K^T
+  auto role_a = [&](int i0, int q4, int g3, int p2) {
+    row_product(Qs[q4], nullptr);                          // S = Q K^T
     uint32_t keep_from[4] = {0, 0, 0, 0};
     if constexpr (DROPOUT) {
       // a lane draws for query (r % 4) of each group of four consecutive queries; the four
@@ -216,7 +220,7 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
     for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
       for (int i4 = 0; i4 < 4; ++i4) {
-        const f32x4 l4 = *(const f32x4*)(&Ls[p2][32 * qb + 8 * i4 + 4 * g]);
+        const f32x4 l4 = *(const f32x4*)(&Ls[g3][32 * qb + 8 * i4 + 4 * g]);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int i = 4 * i4 + e;
@@ -232,11 +236,11 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
       }
 #pragma unroll
     for (int cc = 0; cc < 4; ++cc) Px[p2][pair][cc][lane] = pfull[cc];
-    if constexpr (DROPOUT) col_product(Gs[p2], pf);        // dV^T += dO^T P_dropped
-    else col_product(Gs[p2], pfull);
+    if constexpr (DROPOUT) col_product(Gs[g3], pf);        // dV^T += dO^T P_dropped
+    else col_product(Gs[g3], pfull);
   };
   // ---- role B, second half for the previous tile: dS from sd (= dP) and A's P, then dK
-  auto role_b_ds_dk = [&](int q3, int p2) {
+  auto role_b_ds_dk = [&](int q4, int p2) {
     uint32_t keep_from[4] = {0, 0, 0, 0};
     if constexpr (DROPOUT) keep_from_word(Kw[p2][pair][lane], keep_from);
     T8 pin[4], dsf[4];
@@ -247,7 +251,7 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
 #pragma unroll
       for (int i4 = 0; i4 < 4; ++i4) {
         f32x4 d4 = {0.f, 0.f, 0.f, 0.f};
-        if constexpr (DROPOUT) d4 = *(const f32x4*)(&Ds[q3][32 * qb + 8 * i4 + 4 * g]);   // -D_i
+        if constexpr (DROPOUT) d4 = *(const f32x4*)(&Ds[q4][32 * qb + 8 * i4 + 4 * g]);   // -D_i
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int i = 4 * i4 + e;
@@ -260,37 +264,47 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
           dsf[cc][t] = (T)((float)pin[cc][t] * dpv);
         }
       }
-    col_product(Qs[q3], dsf);                               // dK^T += Q^T dS
+    col_product(Qs[q4], dsf);                               // dK^T += Q^T dS
   };
 
   // ---- pipeline over the tiles of this key block
   int t0 = it.next();
-  if (t0 >= 0) fetch_tile(t0, 0, 0);
-  int q3 = 0, p2 = 0;          // buffer indices of the current tile: j % 3 and j % 2
+  int t1 = t0 >= 0 ? it.next() : -1;
+  if (!role_b) {
+    if (t0 >= 0) fetch_tile(t0, 0, 0);
+    if (t1 >= 0) fetch_tile(t1, 1, 1);
+  }
+  int q4 = 0, g3 = 0, p2 = 0;  // ring slots of the current tile: j % 4, j % 3, j % 2
   bool have_prev = false, prev_active = false;
   while (t0 >= 0) {
-    wait_async_copies();       // this wavefront's share of tile t0 has landed ...
-    __syncthreads();           // ... and so has everyone else's; the buffers of tile t0 - 2 are free
-    const int t1 = it.next();
-    const int q3n = q3 == 2 ? 0 : q3 + 1;
-    if (t1 >= 0) fetch_tile(t1, q3n, p2 ^ 1);
+    if (!role_b) {
+      // tile t0 must have landed; the copies of t1, issued after it, may still be in flight
+      if (t1 < 0) wait_async_copies();
+      else if (wave == 1 || wave == 2) wait_async_copies_but<kTileCopies + 1>();
+      else wait_async_copies_but<kTileCopies>();
+    }
+    __syncthreads();           // tile t0 is visible to everyone; the slots of tile t0 - 2 are free
+    const int t2 = t1 >= 0 ? it.next() : -1;
     const int i0 = t0 * TILE;
     const bool active = !CAUSAL || i0 + TILE - 1 >= kw0;
     if (!role_b) {
-      if (active) role_a(i0, q3, p2);
+      if (active) role_a(i0, q4, g3, p2);
+      if (t2 >= 0) fetch_tile(t2, (q4 + 2) & 3, g3 == 0 ? 2 : g3 - 1);   // slots (j + 2) % 4, (j + 2) % 3
     } else {
-      if (have_prev && prev_active) role_b_ds_dk(q3 == 0 ? 2 : q3 - 1, p2 ^ 1);
+      if (have_prev && prev_active) role_b_ds_dk((q4 + 3) & 3, p2 ^ 1);
       // dP = dO V^T; without dropout it starts from -D, so the result is dP - D
-      if (active) row_product(Gs[p2], DROPOUT ? nullptr : Ds[q3]);
+      if (active) row_product(Gs[g3], DROPOUT ? nullptr : Ds[q4]);
     }
     have_prev = true;
     prev_active = active;
     t0 = t1;
-    q3 = q3n;
+    t1 = t2;
+    q4 = (q4 + 1) & 3;
+    g3 = g3 == 2 ? 0 : g3 + 1;
     p2 ^= 1;
   }
   __syncthreads();
-  if (role_b && have_prev && prev_active) role_b_ds_dk(q3 == 0 ? 2 : q3 - 1, p2 ^ 1);
+  if (role_b && have_prev && prev_active) role_b_ds_dk((q4 + 3) & 3, p2 ^ 1);
 
   const float out_scale = role_b ? a.tau : (DROPOUT ? a.keep_scale : 1.f);
   if (SPARSE && heavy) {

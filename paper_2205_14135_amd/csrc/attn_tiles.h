@@ -95,6 +95,15 @@ __device__ __forceinline__ void wait_async_copies() {
   asm volatile("" ::: "memory");
 #endif
 }
+// Waits until at most N of this wavefront's vector-memory operations are outstanding (they
+// complete in order, so the N most recent copies may still be in flight).
+template <int N> __device__ __forceinline__ void wait_async_copies_but() {
+#if defined(__HIP_DEVICE_COMPILE__)
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  __builtin_amdgcn_s_waitcnt((N & 15) | 0x0F70 | ((N >> 4) << 14));
+  asm volatile("" ::: "memory");
+#endif
+}
 __device__ __forceinline__ uint32_t lds_addr(const void* p) {
   return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)p;
 }
