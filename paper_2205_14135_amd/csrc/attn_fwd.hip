@@ -158,10 +158,19 @@ __global__ __launch_bounds__(NT, 2) void fwd_kernel(const KArgs a) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[kb][i]);
       mx = fmaxf(mx, xchg32(mx));
-      const float m_new = fmaxf(m_run, mx * c);
-      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
-      m_run = m_new;
+      // rescale only when some row of this wavefront saw a new maximum (wavefront-uniform branch)
+      if (__builtin_amdgcn_ballot_w64(mx * c > m_run) != 0) {
+        const float m_new = fmaxf(m_run, mx * c);
+        const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
+        m_run = m_new;
+        l_run *= alpha;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
+      }
+      const float m_use = (m_run == -INFINITY) ? 0.f : m_run;
       float psum = 0.f;
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
@@ -171,11 +180,7 @@ __global__ __launch_bounds__(NT, 2) void fwd_kernel(const KArgs a) {
           s[kb][i] = p;
           psum += p;
         }
-      l_run = l_run * alpha + psum;
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
+      l_run += psum;
       // ---- dropout on the unnormalised probabilities (the row sum above is undropped)
       if constexpr (DROPOUT) {
 #pragma unroll

@@ -164,7 +164,9 @@ __global__ __launch_bounds__(NT) void fwd_pp_kernel(const KArgs a) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[kb][i]);
     mx = fmaxf(mx, xchg32(mx)) * c;
-    // rescale only when some row of this wavefront saw a new maximum (wavefront-uniform branch)
+    // rescale only when some row of this wavefront saw a new maximum (wavefront-uniform branch).
+    // The reference must be the true running maximum: then the largest probability of a row is
+    // exactly 1 in 16 bits, which is what keeps peaked rows within the forward tolerance.
     if (__builtin_amdgcn_ballot_w64(mx > m_run) != 0) {
       const float m_new = fmaxf(m_run, mx);
       const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
