@@ -93,7 +93,7 @@ def flops_fwd(cfg, nnz_blocks=None):
     return f * (0.5 if cfg["causal"] else 1.0)
 
 
-def run_gpu(cfg, steps, warmup, seed):
+def run_gpu(cfg, steps, warmup, seed, mask_override=None):
     import numpy as np
     import torch
     from paper_2205_14135_amd import binding, inputs
@@ -109,7 +109,7 @@ def run_gpu(cfg, steps, warmup, seed):
     bm = bm_np = None
     nnz = None
     if cfg["sparse"]:
-        bm_np = inputs.butterfly_block_mask(N // 128)
+        bm_np = inputs.butterfly_block_mask(N // 128) if mask_override is None else mask_override
         bm = torch.from_numpy(bm_np).to(dev)
         nnz = int(bm_np.sum())
     O = torch.empty_like(g["Q"])
@@ -163,7 +163,86 @@ def run_gpu(cfg, steps, warmup, seed):
             dur[n] += hev.elapsed_ms(e[i], e[i + 1])
     dur = {n: v / steps for n, v in dur.items()}
     hev.close()
-    return dict(ms_per_step=wall_ms / steps, kernel_ms=dur, names=names, nnz=nnz, tensors=t, block_mask=bm_np, tau=tau)
+    peak_bytes = torch.cuda.max_memory_allocated(dev)
+    return dict(ms_per_step=wall_ms / steps, kernel_ms=dur, names=names, nnz=nnz, tensors=t, block_mask=bm_np, tau=tau,
+                peak_bytes=peak_bytes)
+
+
+def sparsity_sweep(steps):
+    """Runtime of the block-sparse path against the fraction of kept 128x128 blocks (the shape
+    of Fig. 2, right: N = 4096; here B=4, H=16, d=128, bf16), random masks that keep the diagonal,
+    next to the dense kernels on the same inputs.  One JSON line per density on stderr."""
+    import numpy as np
+    from paper_2205_14135_amd import inputs
+    base = dict(B=4, H=16, N=4096, d=128, dtype="bf16", causal=False, p=0.0)
+    T = base["N"] // 128
+    dense = run_gpu(dict(base, sparse=False), steps, 2, inputs.BASE_SEED + 3)
+    dk = [dense["kernel_ms"][n] for n in dense["names"]]
+    print(json.dumps(dict(density=None, kernel="dense", fwd_ms=round(dk[0], 4), bwd_ms=round(sum(dk[1:]), 4))),
+          file=sys.stderr, flush=True)
+    rng = np.random.default_rng(inputs.BASE_SEED + 77)
+    for dens in (0.05, 0.1, 0.2, 0.4, 0.6, 0.8, 1.0):
+        m = (rng.random((T, T)) < dens).astype(np.uint8)
+        np.fill_diagonal(m, 1)
+        r = run_gpu(dict(base, sparse=True), steps, 2, inputs.BASE_SEED + 3, mask_override=m)
+        k = [r["kernel_ms"][n] for n in r["names"]]
+        frac = float(m.mean())
+        print(json.dumps(dict(density=round(frac, 4), kept_blocks=int(m.sum()), fwd_ms=round(k[0], 4),
+                              bwd_ms=round(sum(k[1:]), 4),
+                              fwd_ms_per_density=round(k[0] / frac, 4), bwd_ms_per_density=round(sum(k[1:]) / frac, 4))),
+              file=sys.stderr, flush=True)
+
+
+def memory_and_naive(steps):
+    """Device memory and time of this library against a plain materialise-S attention written with
+    PyTorch ops (Algorithm 0 of the paper: S = QK^T, P = softmax(S), O = PV, autograd backward),
+    H=16, d=128, bf16, B*N = 16384 tokens.  PyTorch is used here as the comparison system only.
+    One JSON line per N on stderr."""
+    import torch
+    from paper_2205_14135_amd import inputs
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    torch.zeros(1, device=dev)      # initialises the allocator before its statistics are reset
+    for n in (512, 1024, 2048, 4096, 8192):
+        cfg = dict(B=16384 // n, H=16, N=n, d=128, dtype="bf16", causal=False, p=0.0, sparse=False)
+        torch.cuda.empty_cache()
+        torch.cuda.reset_peak_memory_stats(dev)
+        base_alloc = torch.cuda.memory_allocated(dev)
+        r = run_gpu(cfg, steps, 2, inputs.BASE_SEED + 3)
+        ours_peak = r["peak_bytes"] - base_alloc
+        ours_ms = sum(r["kernel_ms"].values())
+        io_bytes = 8 * cfg["B"] * cfg["H"] * n * 128 * 2          # Q K V dO O dQ dK dV
+        del r
+        torch.cuda.empty_cache()
+        g = {k: torch.randn(cfg["B"], 16, n, 128, device=dev, dtype=torch.bfloat16, requires_grad=(k != "dO"))
+             for k in ("Q", "K", "V", "dO")}
+        tau = 1.0 / math.sqrt(128)
+
+        def naive():
+            S = torch.matmul(g["Q"], g["K"].transpose(-1, -2)) * tau
+            P = torch.softmax(S, dim=-1)
+            O = torch.matmul(P, g["V"])
+            O.backward(g["dO"])
+            for k in ("Q", "K", "V"):
+                g[k].grad = None
+        naive()
+        torch.cuda.synchronize()
+        torch.cuda.reset_peak_memory_stats(dev)
+        before = torch.cuda.memory_allocated(dev)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            naive()
+        e1.record()
+        torch.cuda.synchronize()
+        naive_ms = e0.elapsed_time(e1) / steps
+        naive_extra = torch.cuda.max_memory_allocated(dev) - before
+        print(json.dumps(dict(N=n, B=cfg["B"], tensors_MiB=round(io_bytes / 2**20, 1),
+                              ours_extra_MiB=round((ours_peak - io_bytes) / 2**20, 1),
+                              naive_extra_MiB=round(naive_extra / 2**20, 1),
+                              ours_fwd_bwd_ms=round(ours_ms, 4), naive_fwd_bwd_ms=round(naive_ms, 4),
+                              speedup=round(naive_ms / ours_ms, 2))), file=sys.stderr, flush=True)
+        del g
 
 
 def cpu_baseline(cfg, run, budget_s=12.0, max_s=30.0):
@@ -234,6 +313,10 @@ def main():
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep", action="store_true", help="also time every sweep point (extra JSON lines on stderr)")
+    ap.add_argument("--sparsity-sweep", action="store_true",
+                    help="only: block-sparse runtime against mask density at N=4096 (JSON lines on stderr)")
+    ap.add_argument("--memory-table", action="store_true",
+                    help="only: memory and time against a materialise-S attention in PyTorch ops (JSON lines on stderr)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a 1 GiB elementwise copy kernel (reference for the HBM byte counters)")
     args = ap.parse_args()
@@ -259,6 +342,12 @@ def main():
         return
     from paper_2205_14135_amd import binding, inputs
     binding.load()
+    if args.sparsity_sweep:
+        sparsity_sweep(max(3, args.steps // 3))
+        return
+    if args.memory_table:
+        memory_and_naive(max(3, args.steps // 3))
+        return
 
     if args.sweep:
         for name in sorted(wl):

@@ -35,7 +35,7 @@ __global__ __launch_bounds__(256) void rowdot_kernel(const KArgs a) {
   constexpr int CPR = D / 8;  // lanes per row
   const int64_t rows = (int64_t)a.B * a.H * a.N;
   const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (gid == 0 && a.seglist != nullptr) a.seglist[0] = 0;   // block-sparse: empty segment list
+  if (gid == 0 && a.seglist != nullptr) { a.seglist[0] = 0; a.seglist[1] = 0; }   // block-sparse: empty segment list, no blocks counted
   const int64_t row = gid / CPR;
   const int ch = (int)(gid % CPR);
   float acc = 0.f;

@@ -43,7 +43,7 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
   const int n_kt = a.N / 128;
   // Work assignment.  Dense: one key block per workgroup.  Block-sparse: the first 8 * chunk
   // workgroups take one mask column each and leave the heavy ones (many kept blocks, e.g. a
-  // global-token column) alone; those were cut into segments by sparse_prep_kernel and the
+  // global-token column) alone; those were cut into segments by sparse_plan_kernel and the
   // remaining workgroups walk that segment list.
   const int n_col_groups = kXcds * a.chunk;
   const bool list_mode = SPARSE && (int)blockIdx.x >= n_col_groups;
@@ -54,12 +54,12 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
     item = xcd_item(a.n_items, a.chunk);
     if (item < 0) return;
     if constexpr (SPARSE) {
-      if (a.colcnt[item] > kHeavyBlocks) return;
+      if (a.colcnt[item] > a.seglist[2]) return;
     }
   } else {
     const int idx = ((int)blockIdx.x - n_col_groups) + round * ((int)gridDim.x - n_col_groups);
     if (idx >= a.seglist[0]) return;
-    const int e = a.seglist[1 + idx];
+    const int e = a.seglist[kSegHeader + idx];
     item = e / kMaxSegs;
     const int seg = e % kMaxSegs;
     const int cnt = a.colcnt[item];
@@ -326,10 +326,9 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
   }  // for round
 }
 
-// Block-sparse preparation: kept blocks per mask column (rows >= column under a causal mask),
-// and zeroed fp32 accumulators for the columns that will be split.  One 64-thread group per (bh, kt).
-template <int D>
-__global__ __launch_bounds__(64) void sparse_prep_kernel(const KArgs a) {
+// Block-sparse preparation, step 1: kept blocks per mask column (rows >= column under a causal
+// mask) and their total.  One 64-thread group per (bh, kt).
+__global__ __launch_bounds__(64) void sparse_count_kernel(const KArgs a) {
   const int item = blockIdx.x;
   const int n_kt = a.T;
   const int bh = item / n_kt, kt = item % n_kt;
@@ -344,12 +343,27 @@ __global__ __launch_bounds__(64) void sparse_prep_kernel(const KArgs a) {
     const bool on = blk < limit && col[(int64_t)blk * a.T] != 0;
     cnt += __builtin_popcountll(__ballot(on));
   }
-  if (threadIdx.x == 0) a.colcnt[item] = cnt;
-  if (cnt > kHeavyBlocks) {
+  if (threadIdx.x == 0) {
+    a.colcnt[item] = cnt;
+    if (cnt > 0) atomicAdd(a.seglist + 1, cnt);
+  }
+}
+
+// Step 2: the heavy threshold, the segment list of the heavy columns and zeroed fp32
+// accumulators for them.  One 64-thread group per (bh, kt).
+template <int D>
+__global__ __launch_bounds__(64) void sparse_plan_kernel(const KArgs a) {
+  const int item = blockIdx.x;
+  const int n_kt = a.T;
+  const int bh = item / n_kt, kt = item % n_kt;
+  const int thr = max((int)kHeavyBlocks, a.seglist[1] / (2 * kComputeUnits));
+  if (item == 0 && threadIdx.x == 0) a.seglist[2] = thr;
+  const int cnt = a.colcnt[item];
+  if (cnt > thr) {
     if (threadIdx.x == 0) {
       const int nseg = min((int)kMaxSegs, (cnt + kSegBlocks - 1) / kSegBlocks);
       const int at = atomicAdd(a.seglist, nseg);
-      for (int sgi = 0; sgi < nseg; ++sgi) a.seglist[1 + at + sgi] = item * kMaxSegs + sgi;
+      for (int sgi = 0; sgi < nseg; ++sgi) a.seglist[kSegHeader + at + sgi] = item * kMaxSegs + sgi;
     }
     const int64_t off = ((int64_t)bh * a.N + (int64_t)kt * 128) * D;
     for (int i = threadIdx.x; i < 128 * D / 4; i += 64) {
@@ -365,7 +379,7 @@ template <typename T, int D>
 __global__ __launch_bounds__(256) void sparse_finish_kernel(const KArgs a) {
   typedef typename Vec<T>::x4 T4;
   const int item = blockIdx.x;
-  if (a.colcnt[item] <= kHeavyBlocks) return;
+  if (a.colcnt[item] <= a.seglist[2]) return;
   const int n_kt = a.T;
   const int bh = item / n_kt, kt = item % n_kt;
   const int64_t head_off = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
@@ -388,7 +402,8 @@ int launch_td(KArgs a, bool causal, bool dropout, bool sparse, hipStream_t s) {
   const int cols = a.B * a.H * a.T;
   if (sparse) {
     a.causal = causal;
-    hipLaunchKernelGGL((sparse_prep_kernel<D>), dim3(cols), dim3(64), 0, s, a);
+    hipLaunchKernelGGL(sparse_count_kernel, dim3(cols), dim3(64), 0, s, a);
+    hipLaunchKernelGGL((sparse_plan_kernel<D>), dim3(cols), dim3(64), 0, s, a);
     const int e = (int)hipGetLastError();
     if (e != 0) return e;
   }

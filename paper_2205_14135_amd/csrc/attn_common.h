@@ -25,7 +25,8 @@ struct KArgs {
   float* Dvec;             // bwd scratch: -D_i = -rowsum(dO_i o O_i)   [B,H,N]
   float* L2vec;            // bwd scratch: L_i * log2(e), +inf where L_i = -inf   [B,H,N]
   int* colcnt;             // block-sparse bwd scratch: kept blocks per mask column   [B*H, T]
-  int* seglist;            // block-sparse bwd scratch: [0] = number of entries, then (column * kMaxSegs + segment)
+  int* seglist;            // block-sparse bwd scratch: [0] = number of entries, [1] = kept blocks in total,
+                           // [2] = heavy threshold, from [kSegHeader]: entries (column * kMaxSegs + segment)
   float* dKacc;            // block-sparse bwd scratch: fp32 dK / dV of the columns that are
   float* dVacc;            //   split over several workgroups                         [B,H,N,d]
   int causal;              // causal flag for the kernels that are not specialised on it
@@ -45,9 +46,11 @@ struct KArgs {
 };
 
 enum { kXcds = 8, kMaskBlock = 128 };
-// Block-sparse dK/dV: a mask column with more than kHeavyBlocks kept blocks is split into
-// segments of about kSegBlocks blocks (at most kMaxSegs), one workgroup each, summed with fp32 atomics.
-enum { kHeavyBlocks = 24, kSegBlocks = 12, kMaxSegs = 32 };
+// Block-sparse dK/dV: a mask column is "heavy" when it keeps more than kHeavyBlocks blocks AND
+// more than half of a compute unit's fair share of all kept blocks (so a mask whose columns are
+// all long, e.g. a dense one, is not split at all).  Heavy columns are cut into segments of about
+// kSegBlocks blocks (at most kMaxSegs), one workgroup each, summed with fp32 atomics.
+enum { kHeavyBlocks = 24, kSegBlocks = 12, kMaxSegs = 32, kSegHeader = 8, kComputeUnits = 256 };
 
 // Launchers (defined in the .hip files).  dtype: 0 fp16, 1 bf16.  Return hipError_t as int.
 int launch_fwd(const KArgs& a, int dtype, int d, bool causal, bool dropout, bool sparse, hipStream_t s);
