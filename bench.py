@@ -153,9 +153,9 @@ def run_gpu(cfg, steps, warmup, seed, mask_override=None):
     elif cfg["p"] > 0:
         use_pp = d == 128
     elif d == 128:
-        use_pp = N >= (4096 if cfg["causal"] else 512)
+        use_pp = N >= 512
     else:
-        use_pp = N >= (8192 if cfg["causal"] else 2048)
+        use_pp = N >= (1024 if cfg["causal"] else 2048)
     names = ["fwd_pp_kernel" if use_pp else "fwd_kernel", "rowdot_kernel", "dq_kernel", "dkv_rs_kernel"]
     dur = {n: 0.0 for n in names}
     for e in evs:

@@ -75,8 +75,19 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const KArgs a) {
   const int item = xcd_item(a.n_items, a.chunk);
   if (item < 0) return;
   const int n_qt = a.N / 128;
-  const int bh = item / n_qt;
-  const int qt = CAUSAL ? (n_qt - 1 - item % n_qt) : item % n_qt;
+  // Work item = (head, row block).  Under the causal mask row block q sweeps 2 (q + 1) key tiles;
+  // for dense d = 64 problems an item is the pair (n_qt - 1 - q, q), one per pass, so that every
+  // workgroup does the same amount of work (at d = 128 the loop costs registers the kernel does
+  // not have).
+  constexpr bool PAIRED = CAUSAL && !SPARSE && D == 64;
+  const int n_per_head = PAIRED ? (n_qt + 1) / 2 : n_qt;
+  const int bh = item / n_per_head;
+  const int q_item = item % n_per_head;
+  const int n_pass = PAIRED && q_item != n_qt - 1 - q_item ? 2 : 1;
+#pragma clang loop unroll(disable)
+  for (int pass = 0; pass < n_pass; ++pass) {
+  if (pass) __syncthreads();   // the tile buffers staged the first block's output rows
+  const int qt = PAIRED ? (pass ? q_item : n_qt - 1 - q_item) : (CAUSAL ? n_qt - 1 - q_item : q_item);
   const int b = bh / a.H, h = bh % a.H;
   const int64_t head_off = (int64_t)b * a.sb + (int64_t)h * a.sh;
   const T* __restrict__ Kg = (const T*)a.K + head_off;
@@ -231,6 +242,7 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const KArgs a) {
   // the loop ends on a barrier (or never touched LDS): the tile buffers stage the output rows
   T* stage = (wave < 2 ? &Ks[0][0] + wave * 32 * D : &Vs[0][0] + (wave - 2) * 32 * D);
   store_rows_coalesced<T, D>(stage, (T*)a.dQ + head_off + (int64_t)q0 * a.sn, a.sn, dq, a.tau);
+  }  // for pass
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -399,6 +411,13 @@ int launch_bwd_td(const KArgs& a, bool causal, bool dropout, bool sparse, hipStr
   if (e != 0) return e;
   if (ev) (void)hipEventRecord(ev[1], s);
   const dim3 grid(kXcds * a.chunk), block(NT);
+  // dense causal d = 64 dQ items are pairs of row blocks
+  KArgs aq = a;
+  if (causal && !sparse && D == 64) {
+    aq.n_items = a.B * a.H * ((a.N / 128 + 1) / 2);
+    aq.chunk = (aq.n_items + kXcds - 1) / kXcds;
+  }
+  const dim3 grid_q(kXcds * aq.chunk);
   // ATTN_DKV_VARIANT=base selects the single-role dK/dV kernel of this file instead of the
   // role-split one (bench-time comparison)
   static const bool dkv_base = [] {
@@ -407,7 +426,7 @@ int launch_bwd_td(const KArgs& a, bool causal, bool dropout, bool sparse, hipStr
   }();
 #define ATTN_BWD_CASE(C, P, S)                                                   \
   if (causal == C && dropout == P && sparse == S) {                              \
-    hipLaunchKernelGGL((dq_kernel<T, D, C, P, S>), grid, block, 0, s, a);        \
+    hipLaunchKernelGGL((dq_kernel<T, D, C, P, S>), grid_q, block, 0, s, aq);     \
     e = (int)hipGetLastError();                                                  \
     if (e != 0) return e;                                                        \
     if (ev) (void)hipEventRecord(ev[2], s);                                      \

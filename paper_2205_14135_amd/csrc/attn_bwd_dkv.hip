@@ -41,20 +41,29 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
   __shared__ uint32_t Kw[2][4][64];                                // dropout keep words [buf][pair][lane]
 
   const int n_kt = a.N / 128;
-  // Work assignment.  Dense: one key block per workgroup.  Block-sparse: the first 8 * chunk
+  // Work assignment.  Dense: one key block per workgroup; under the causal mask key block k is
+  // visited by N/64 - 2k query tiles, so a workgroup takes the pair (k, n_kt - 1 - k), one per
+  // round, and all workgroups do the same amount of work.  Block-sparse: the first 8 * chunk
   // workgroups take one mask column each and leave the heavy ones (many kept blocks, e.g. a
   // global-token column) alone; those were cut into segments by sparse_plan_kernel and the
   // remaining workgroups walk that segment list.
   const int n_col_groups = kXcds * a.chunk;
   const bool list_mode = SPARSE && (int)blockIdx.x >= n_col_groups;
+  constexpr bool PAIRED = CAUSAL && !SPARSE;
+  const int n_pair = (n_kt + 1) / 2;
   for (int round = 0;; ++round) {
   int item, skip_blocks = 0, take_blocks = 0x7fffffff;
-  bool heavy = false;
+  bool heavy = false, last_round = true;
   if (!list_mode) {
     item = xcd_item(a.n_items, a.chunk);
     if (item < 0) return;
     if constexpr (SPARSE) {
       if (a.colcnt[item] > a.seglist[2]) return;
+    }
+    if constexpr (PAIRED) {
+      const int q = item % n_pair;
+      last_round = round == 1 || q == n_kt - 1 - q;
+      item = (item / n_pair) * n_kt + (round == 0 ? q : n_kt - 1 - q);
     }
   } else {
     const int idx = ((int)blockIdx.x - n_col_groups) + round * ((int)gridDim.x - n_col_groups);
@@ -321,8 +330,8 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
     store_rows_coalesced<T, D>(stage, (T*)(role_b ? a.dK : a.dV) + head_off + (int64_t)kw0 * a.sn, a.sn, acc,
                                out_scale);
   }
-  if (!list_mode) return;
-  __syncthreads();   // LDS is reused by the next segment
+  if (!list_mode && last_round) return;
+  __syncthreads();   // LDS is reused by the next segment / key block
   }  // for round
 }
 
@@ -408,6 +417,10 @@ int launch_td(KArgs a, bool causal, bool dropout, bool sparse, hipStream_t s) {
     if (e != 0) return e;
   }
   // block-sparse: kListGroups extra workgroups walk the list of heavy-column segments
+  if (causal && !sparse) {   // items are pairs of key blocks
+    a.n_items = a.B * a.H * ((a.T + 1) / 2);
+    a.chunk = (a.n_items + kXcds - 1) / kXcds;
+  }
   const dim3 grid(kXcds * a.chunk + (sparse ? kListGroups : 0)), block(NT);
 #define ATTN_DKV_CASE(C, P, S)                                                    \
   if (causal == C && dropout == P && sparse == S) {                               \

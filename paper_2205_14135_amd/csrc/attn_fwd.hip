@@ -295,8 +295,8 @@ int launch_fwd(const KArgs& a, int dtype, int d, bool causal, bool dropout, bool
   }();
   bool use_pp;
   if (dropout) use_pp = d == 128;
-  else if (d == 128) use_pp = a.N >= (causal ? 4096 : 512);
-  else use_pp = a.N >= (causal ? 8192 : 2048);
+  else if (d == 128) use_pp = a.N >= 512;
+  else use_pp = a.N >= (causal ? 1024 : 2048);
   if (variant == 'b') use_pp = false;
   if (variant == 'p') use_pp = true;
   if (!sparse && use_pp) return launch_fwd_pp(a, dtype, d, causal, dropout, s);

@@ -27,20 +27,13 @@ constexpr int BRW = 256;  // query rows per workgroup
 constexpr int BC = 64;    // keys per tile
 constexpr int NT = 512;
 
+// One block of 256 query rows (row block qt of head bh) against all the keys it sees.
 template <typename T, int D, bool CAUSAL, bool DROPOUT>
-__global__ __launch_bounds__(NT) void fwd_pp_kernel(const KArgs a) {
+__device__ __forceinline__ void fwd_pp_rows(const KArgs& a, const int bh, const int qt, T (&Ks)[2][BC * D],
+                                            T (&Vs)[2][BC * D]) {
   typedef typename Vec<T>::x8 T8;
   typedef typename Vec<T>::x4 T4;
   constexpr int KK = D / 16, DB = D / 32;
-
-  __shared__ __attribute__((aligned(16))) T Ks[2][BC * D];
-  __shared__ __attribute__((aligned(16))) T Vs[2][BC * D];
-
-  const int item = xcd_item(a.n_items, a.chunk);
-  if (item < 0) return;
-  const int n_qt = (a.N + BRW - 1) / BRW;
-  const int bh = item / n_qt;
-  const int qt = CAUSAL ? (n_qt - 1 - item % n_qt) : item % n_qt;
   const int b = bh / a.H, h = bh % a.H;
   const int64_t head_off = (int64_t)b * a.sb + (int64_t)h * a.sh;
   const T* __restrict__ Qg = (const T*)a.Q + head_off;
@@ -262,10 +255,33 @@ __global__ __launch_bounds__(NT) void fwd_pp_kernel(const KArgs a) {
   }
 }
 
+// Work item = (head, row block).  Under the causal mask row block q sees 4 (q + 1) key tiles, so
+// an item takes the pair (q, n_qt - 1 - q): every workgroup then does the same amount of work
+// and the static assignment of items to compute units stays balanced.
+template <typename T, int D, bool CAUSAL, bool DROPOUT>
+__global__ __launch_bounds__(NT) void fwd_pp_kernel(const KArgs a) {
+  __shared__ __attribute__((aligned(16))) T Ks[2][BC * D];
+  __shared__ __attribute__((aligned(16))) T Vs[2][BC * D];
+  const int item = xcd_item(a.n_items, a.chunk);
+  if (item < 0) return;
+  const int n_qt = (a.N + BRW - 1) / BRW;
+  if constexpr (CAUSAL) {
+    const int n_pair = (n_qt + 1) / 2;
+    const int bh = item / n_pair, q = item % n_pair;
+    fwd_pp_rows<T, D, CAUSAL, DROPOUT>(a, bh, n_qt - 1 - q, Ks, Vs);
+    if (q != n_qt - 1 - q) {
+      __syncthreads();   // the tile buffers staged the first block's output rows
+      fwd_pp_rows<T, D, CAUSAL, DROPOUT>(a, bh, q, Ks, Vs);
+    }
+  } else {
+    fwd_pp_rows<T, D, CAUSAL, DROPOUT>(a, item / n_qt, item % n_qt, Ks, Vs);
+  }
+}
+
 template <typename T, int D>
 int launch_td(KArgs a, bool causal, bool dropout, hipStream_t s) {
   const int n_qt = (a.N + BRW - 1) / BRW;
-  a.n_items = a.B * a.H * n_qt;
+  a.n_items = a.B * a.H * (causal ? (n_qt + 1) / 2 : n_qt);
   a.chunk = (a.n_items + kXcds - 1) / kXcds;
   const dim3 grid(kXcds * a.chunk), block(NT);
   if (!causal && !dropout) hipLaunchKernelGGL((fwd_pp_kernel<T, D, false, false>), grid, block, 0, s, a);
