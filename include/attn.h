@@ -86,11 +86,13 @@ typedef struct {
 /*
  * Dropout mask (bit-exact contract, shared with nothing but this text):
  * Philox-4x32 with 10 rounds (Salmon et al., SC'11), key = (seed low word,
- * seed high word), counter = (j / 4, i, b * H + h, offset low word) for query
- * row i and key column j of head (b, h); element (i, j) takes output word
- * j % 4 and is KEPT iff word >= floor((double)dropout_p * 2^32).  Kept
- * probabilities are multiplied by 1 / (1 - dropout_p).  The mask depends on
- * indices only, so the backward pass regenerates it (Appendix B.4, obs. 1).
+ * seed high word), counter = (j / 8, i, b * H + h, offset low word) for query
+ * row i and key column j of head (b, h); element (i, j) takes the 16-bit
+ * field f = j % 8 of the 128-bit output (bits [16 (f % 2), 16 (f % 2) + 15]
+ * of output word f / 2) and is KEPT iff field >= floor((double)dropout_p *
+ * 2^16).  Kept probabilities are multiplied by 1 / (1 - dropout_p).  The
+ * mask depends on indices only, so the backward pass regenerates it
+ * (Appendix B.4, obs. 1).
  */
 
 /*

@@ -93,15 +93,16 @@ def philox4x32_10(c0, c1, c2, c3, k0, k1):
 
 
 def dropout_threshold(p_drop) -> int:
-    """Integer threshold: an element is KEPT iff its 32-bit word >= threshold.
+    """Integer threshold: an element is KEPT iff its 16-bit field >= threshold.
 
     The probability travels through the C interface as a float32, so the
-    threshold is floor(double(float32(p)) * 2^32); P(drop) = threshold / 2^32.
+    threshold is floor(double(float32(p)) * 2^16); P(drop) = threshold / 2^16,
+    within 2^-16 of p.
     """
     p = float(np.float32(p_drop))
     if not (0.0 <= p < 1.0):
         raise ValueError("dropout probability must be in [0, 1)")
-    return int(np.floor(p * 4294967296.0))
+    return int(np.floor(p * 65536.0))
 
 
 def dropout_keep_mask(b, h, H, N, p_drop, seed, offset, rows=None):
@@ -110,8 +111,11 @@ def dropout_keep_mask(b, h, H, N, p_drop, seed, offset, rows=None):
     Keying (a reading; the paper only says the generator state is saved and
     the mask regenerated, Appendix B.4 observation 1):
       key     = (seed & 0xffffffff, seed >> 32)
-      counter = (j // 4, i, b * H + h, offset & 0xffffffff)
-      element (i, j) uses output word j % 4; keep iff word >= threshold.
+      counter = (j // 8, i, b * H + h, offset & 0xffffffff)
+      element (i, j) uses the 16-bit field j % 8 of the 128-bit output: field f
+      is bits [16 (f % 2), 16 (f % 2) + 15] of output word f // 2;
+      keep iff field >= threshold.
+    One generator call therefore decides eight consecutive keys of a query.
     i is the query row and j the key column inside the head.  The mask depends
     on indices only: not on tiling, loop order, pass, or other masks.
     """
@@ -123,12 +127,14 @@ def dropout_keep_mask(b, h, H, N, p_drop, seed, offset, rows=None):
     thr = dropout_threshold(p_drop)
     seed = int(seed) & 0xFFFFFFFFFFFFFFFF
     k0, k1 = seed & 0xFFFFFFFF, seed >> 32
-    ngrp = (N + 3) // 4
+    ngrp = (N + 7) // 8
     jg = np.arange(ngrp, dtype=np.int64)[None, :]
     ii = rows[:, None]
     w = philox4x32_10(jg, ii, b * H + h, int(offset) & 0xFFFFFFFF, k0, k1)
-    words = np.stack(w, axis=-1).reshape(rows.size, ngrp * 4)[:, :N]
-    return words >= np.uint32(thr) if thr <= 0xFFFFFFFF else np.zeros_like(words, bool)
+    words = np.stack(w, axis=-1).astype(np.uint32)                       # [rows, ngrp, 4]
+    fields = np.stack([words & np.uint32(0xFFFF), words >> np.uint32(16)], axis=-1)   # [rows, ngrp, 4, 2]
+    fields = fields.reshape(rows.size, ngrp * 8)[:, :N]
+    return fields >= np.uint32(thr)
 
 
 def visible_mask(N, causal=False, block_mask=None, mask_block=128, rows=None, key_length=None):

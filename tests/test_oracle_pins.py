@@ -61,8 +61,9 @@ def test_philox_scalar_reimplementation():
 
 
 def test_dropout_threshold_from_float32():
-    assert orc.dropout_threshold(0.1) == 429496736          # float32(0.1) * 2^32, not 0.1 * 2^32
-    assert orc.dropout_threshold(0.5) == 2 ** 31
+    assert orc.dropout_threshold(0.1) == 6553               # floor(float32(0.1) * 2^16)
+    assert orc.dropout_threshold(0.5) == 2 ** 15
+    assert orc.dropout_threshold(0.999) == 65470            # float32(0.999) = 0.99900001287...
     assert orc.dropout_threshold(0.0) == 0
     with pytest.raises(ValueError):
         orc.dropout_threshold(1.0)
@@ -73,10 +74,12 @@ def test_dropout_mask_keying_and_rate():
     p, seed, off = 0.1, 0x123456789ABCDEF0, 7
     thr = orc.dropout_threshold(p)
     keep = orc.dropout_keep_mask(1, 2, H, N, p, seed, off)
-    # element (i, j): counter (j//4, i, b*H+h, offset), word j%4
-    for (i, j) in [(0, 0), (5, 3), (17, 42), (63, 63), (31, 4)]:
-        w = orc.philox4x32_10(j // 4, i, 1 * H + 2, off, seed & 0xFFFFFFFF, seed >> 32)
-        assert keep[i, j] == (int(w[j % 4]) >= thr)
+    # element (i, j): counter (j//8, i, b*H+h, offset), 16-bit field j%8 (low half of a word first)
+    for (i, j) in [(0, 0), (5, 3), (17, 42), (63, 63), (31, 4), (2, 15), (9, 8)]:
+        w = orc.philox4x32_10(j // 8, i, 1 * H + 2, off, seed & 0xFFFFFFFF, seed >> 32)
+        f = j % 8
+        field = (int(w[f // 2]) >> (16 * (f % 2))) & 0xFFFF
+        assert keep[i, j] == (field >= thr)
     # different heads / seeds / offsets give different masks
     assert (keep != orc.dropout_keep_mask(1, 1, H, N, p, seed, off)).any()
     assert (keep != orc.dropout_keep_mask(1, 2, H, N, p, seed + 1, off)).any()
