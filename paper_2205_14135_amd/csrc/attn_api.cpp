@@ -48,7 +48,7 @@ int check_params(const attn_params* p, Checked* out) {
   k.tau = p->softmax_scale;
   k.scale_log2 = (float)((double)p->softmax_scale * 1.4426950408889634);
   k.keep_scale = 1.0f / (1.0f - p->dropout_p);
-  k.drop_thr = (uint32_t)std::floor((double)p->dropout_p * 4294967296.0);
+  k.drop_thr = (uint32_t)std::floor((double)p->dropout_p * 65536.0);   // 16-bit fields
   k.seed_lo = (uint32_t)(p->seed & 0xFFFFFFFFu);
   k.seed_hi = (uint32_t)(p->seed >> 32);
   k.offset_lo = (uint32_t)(p->offset & 0xFFFFFFFFu);

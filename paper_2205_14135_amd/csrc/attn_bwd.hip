@@ -10,8 +10,8 @@
 //   1. rowdot_kernel : D = rowsum(dO o O), L in base 2                  (HBM-bound, tiny)
 //   2. dq_kernel     : a workgroup owns 128 query rows and sweeps K/V tiles; dQ stays in
 //                      registers (S^T, dP^T layout: lane = query, like the forward kernel)
-//   3. dkv_kernel    : a workgroup owns 128 keys and sweeps Q/dO tiles; dK, dV stay in registers
-//                      (S, dP layout: lane = key)
+//   3. dkv_rs_kernel (attn_bwd_dkv.hip): a workgroup owns 128 keys and sweeps Q/dO tiles;
+//                      dK, dV stay in registers (S, dP layout: lane = key)
 // S and dP are therefore recomputed in both 2 and 3 (seven tile products per (i, j) instead of
 // five) in exchange for no atomics, no fp32 dQ round trip and bit-reproducible gradients.
 #include "attn_common.h"
@@ -23,7 +23,7 @@ namespace attn {
 namespace {
 
 constexpr int NT = 256;
-constexpr int TILE = 64;  // rows of the streamed tile (keys in dq_kernel, queries in dkv_kernel)
+constexpr int TILE = 64;  // keys of the streamed tile
 
 // ---------------------------------------------------------------------------------------------
 // -D_i = -sum_d dO[i][d] * O[i][d] (stored negated: the tile kernels start the dP accumulators
@@ -191,22 +191,22 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const KArgs a) {
             if (k0 + 32 * kb + 8 * (i >> 2) + 4 * g + (i & 3) >= len) s[kb][i] = -INFINITY;
       }
       // P = exp(S - L); dS = P o (dP o Z - D)
+      KeepLQ kq = {0xFFFFFFFFu, 0xFFFFFFFFu};
+      if constexpr (DROPOUT) kq = keep_tile_lane_query(k0, qi, bh, g, a.offset_lo, a.seed_lo, a.seed_hi, a.drop_thr);
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int i4 = 0; i4 < 4; ++i4) {
-          u32x4 w = {0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu};
-          if constexpr (DROPOUT) {
-            const uint32_t jg = (uint32_t)(k0 + 32 * kb + 8 * i4 + 4 * g) >> 2;
-            w = philox4x32_10(jg, (uint32_t)qi, (uint32_t)bh, a.offset_lo, a.seed_lo, a.seed_hi);
-          }
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             const int i = 4 * i4 + e;
             float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][i], c, -l2));
             if (CAUSAL && k0 + 32 * kb + 8 * i4 + 4 * g + e > qi) p = 0.f;
             float dpv = dp[kb][i];
-            if constexpr (DROPOUT) dpv = ((w[e] >= a.drop_thr) ? dpv * a.keep_scale : 0.f) + neg_d;
+            if constexpr (DROPOUT) {
+              const bool keep = (((i4 & 1) ? kq.odd : kq.even) >> (8 * (2 * kb + (i4 >> 1)) + e)) & 1u;
+              dpv = (keep ? dpv * a.keep_scale : 0.f) + neg_d;
+            }
             s[kb][i] = p * dpv;
           }
         }
@@ -245,159 +245,6 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const KArgs a) {
   }  // for pass
 }
 
-// ---------------------------------------------------------------------------------------------
-// dK, dV: workgroup = 128 keys (4 wavefronts x 32), sweep over 64-query tiles.
-template <typename T, int D, bool CAUSAL, bool DROPOUT, bool SPARSE>
-__global__ __launch_bounds__(NT, 1) void dkv_kernel(const KArgs a) {
-  typedef typename Vec<T>::x8 T8;
-  constexpr int KK = D / 16, DB = D / 32;
-  __shared__ __attribute__((aligned(16))) T Qs[TILE * D];
-  __shared__ __attribute__((aligned(16))) T Gs[TILE * D];   // dO tile
-  __shared__ __attribute__((aligned(16))) float Ls[TILE];   // base-2 row statistic
-  __shared__ __attribute__((aligned(16))) float Ds[TILE];   // -D_i
-
-  const int item = xcd_item(a.n_items, a.chunk);
-  if (item < 0) return;
-  const int n_kt = a.N / 128;
-  const int bh = item / n_kt;
-  const int kt = item % n_kt;  // under a causal mask early key blocks are the heavy ones: first
-  const int b = bh / a.H, h = bh % a.H;
-  const int64_t head_off = (int64_t)b * a.sb + (int64_t)h * a.sh;
-  const T* __restrict__ Qg = (const T*)a.Q + head_off;
-  const T* __restrict__ Gg = (const T*)a.dO + head_off;
-  const float* __restrict__ Lg = a.LSE + (int64_t)bh * a.N;
-  const float* __restrict__ Dg = a.Dvec + (int64_t)bh * a.N;
-
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int r = lane & 31, g = lane >> 5;
-  const int kw0 = kt * 128 + wave * 32;
-  const int kj = kw0 + r;  // this lane's key
-
-  T8 kf[KK], vf[KK];  // K^T and V^T fragments (B operands) of this lane's key
-#pragma unroll
-  for (int kk = 0; kk < KK; ++kk) {
-    const int64_t off = head_off + (int64_t)kj * a.sn + 16 * kk + 8 * g;
-    kf[kk] = *(const T8*)((const T*)a.K + off);
-    vf[kk] = *(const T8*)((const T*)a.V + off);
-  }
-  f32x16 dk[DB], dv[DB];
-#pragma unroll
-  for (int db = 0; db < DB; ++db)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) { dk[db][i] = 0.f; dv[db][i] = 0.f; }
-
-  const int len = a.klen ? min(max(a.klen[b], 0), a.N) : a.N;   // key-padding mask
-  TileIter<SPARSE> it;
-  if constexpr (SPARSE)
-    it.init(a.mask + (int64_t)h * a.mask_sh + kt, a.T, CAUSAL ? kt : 0, kt * 128 >= len ? 0 : min(a.T, (len + 127) / 128));
-  else
-    it.init(nullptr, 0, CAUSAL ? 2 * kt : 0, kt * 128 >= len ? 0 : min(a.N / TILE, (len + TILE - 1) / TILE));
-  TrOffsets<D> tro;
-  tro.init();
-  TileStage<T, D, NT> qs, gs;
-  float lreg = 0.f, dreg = 0.f;
-  auto load_stats = [&](int row0) {
-    if (threadIdx.x < TILE) {
-      const float lse = Lg[row0 + threadIdx.x];
-      lreg = (lse == -INFINITY) ? INFINITY : lse * 1.4426950408889634f;
-      dreg = Dg[row0 + threadIdx.x];
-    }
-  };
-
-  const float c = a.scale_log2;
-  int itile = it.next();
-  if (itile >= 0) { qs.load(Qg, a.sn, itile * TILE); gs.load(Gg, a.sn, itile * TILE); load_stats(itile * TILE); }
-  while (itile >= 0) {
-    qs.store(Qs);
-    gs.store(Gs);
-    if (threadIdx.x < TILE) { Ls[threadIdx.x] = lreg; Ds[threadIdx.x] = dreg; }
-    __syncthreads();
-    const int inext = it.next();
-    if (inext >= 0) { qs.load(Qg, a.sn, inext * TILE); gs.load(Gg, a.sn, inext * TILE); load_stats(inext * TILE); }
-
-    const int i0 = itile * TILE;
-    if (!CAUSAL || i0 + TILE - 1 >= kw0) {
-      f32x16 s[2], dp[2];
-#pragma unroll
-      for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) { s[qb][i] = 0.f; dp[qb][i] = 0.f; }
-#pragma unroll
-      for (int kk = 0; kk < KK; ++kk)
-#pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
-          const int off = lds_off<D>(32 * qb + r, 2 * kk + g);
-          s[qb] = mfma32(*(const T8*)(Qs + off), kf[kk], s[qb]);     // S  = Q K^T
-          dp[qb] = mfma32(*(const T8*)(Gs + off), vf[kk], dp[qb]);   // dP = dO V^T
-        }
-      // dropout keep bits: a lane draws for query (r % 4) of each group of four consecutive
-      // queries and the four lanes of a quad (four consecutive keys) exchange the results
-      uint32_t keep_from[4] = {0, 0, 0, 0};
-      if constexpr (DROPOUT) {
-        uint32_t mine = 0;
-#pragma unroll
-        for (int n = 0; n < 8; ++n) {  // n = 4 qb + i4
-          const uint32_t qrow = (uint32_t)(i0 + 32 * (n >> 2) + 8 * (n & 3) + 4 * g + (r & 3));
-          const u32x4 w = philox4x32_10((uint32_t)kj >> 2, qrow, (uint32_t)bh, a.offset_lo, a.seed_lo, a.seed_hi);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) mine |= (w[e] >= a.drop_thr ? 1u : 0u) << (4 * n + e);
-        }
-        // keep_from[e]: bits drawn by the quad lane that handled query e, shifted so that bit 4n
-        // is this lane's key
-        keep_from[0] = (uint32_t)__builtin_amdgcn_mov_dpp((int)mine, 0x00, 0xF, 0xF, true) >> (r & 3);
-        keep_from[1] = (uint32_t)__builtin_amdgcn_mov_dpp((int)mine, 0x55, 0xF, 0xF, true) >> (r & 3);
-        keep_from[2] = (uint32_t)__builtin_amdgcn_mov_dpp((int)mine, 0xAA, 0xF, 0xF, true) >> (r & 3);
-        keep_from[3] = (uint32_t)__builtin_amdgcn_mov_dpp((int)mine, 0xFF, 0xF, 0xF, true) >> (r & 3);
-      }
-      f32x16 pd[2];  // dropped probabilities (without the 1/(1-p) factor, applied at the end)
-#pragma unroll
-      for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-        for (int i4 = 0; i4 < 4; ++i4) {
-          const f32x4 l4 = *(const f32x4*)(Ls + 32 * qb + 8 * i4 + 4 * g);
-          const f32x4 d4 = *(const f32x4*)(Ds + 32 * qb + 8 * i4 + 4 * g);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int i = 4 * i4 + e;
-            float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[qb][i], c, -l4[e]));
-            if ((CAUSAL && kj > i0 + 32 * qb + 8 * i4 + 4 * g + e) || kj >= len) p = 0.f;
-            float dpv = dp[qb][i];
-            float pk = p;
-            if constexpr (DROPOUT) {
-              const bool keep = (keep_from[e] >> (4 * (4 * qb + i4))) & 1u;
-              dpv = keep ? dpv * a.keep_scale : 0.f;
-              pk = keep ? p : 0.f;
-            }
-            pd[qb][i] = pk;
-            s[qb][i] = p * (dpv + d4[e]);   // the scratch vector holds -D
-          }
-        }
-      T8 pf[4], dsf[4];
-#pragma unroll
-      for (int cc = 0; cc < 4; ++cc)
-#pragma unroll
-        for (int t = 0; t < 8; ++t) {
-          pf[cc][t] = (T)pd[cc >> 1][8 * (cc & 1) + t];
-          dsf[cc][t] = (T)s[cc >> 1][8 * (cc & 1) + t];
-        }
-      // dV^T += dO^T P_dropped ;  dK^T += Q^T dS
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int cc = 0; cc < 4; ++cc) {
-          const T* gb = Gs + 16 * cc * D;
-          const T* qb_ = Qs + 16 * cc * D;
-          dv[db] = mfma32(tr_frag<T8>(gb + tro.off[db][0], gb + tro.off[db][1]), pf[cc], dv[db]);
-          dk[db] = mfma32(tr_frag<T8>(qb_ + tro.off[db][0], qb_ + tro.off[db][1]), dsf[cc], dk[db]);
-        }
-    }
-    __syncthreads();
-    itile = inext;
-  }
-  store_rows<T, D>((T*)a.dV + head_off + (int64_t)kj * a.sn, dv, DROPOUT ? a.keep_scale : 1.f, g);
-  store_rows<T, D>((T*)a.dK + head_off + (int64_t)kj * a.sn, dk, a.tau, g);
-}
-
 template <typename T> constexpr int kDtype = 0;
 template <> constexpr int kDtype<__bf16> = 1;
 
@@ -410,7 +257,7 @@ int launch_bwd_td(const KArgs& a, bool causal, bool dropout, bool sparse, hipStr
   int e = (int)hipGetLastError();
   if (e != 0) return e;
   if (ev) (void)hipEventRecord(ev[1], s);
-  const dim3 grid(kXcds * a.chunk), block(NT);
+  const dim3 block(NT);
   // dense causal d = 64 dQ items are pairs of row blocks
   KArgs aq = a;
   if (causal && !sparse && D == 64) {
@@ -418,24 +265,13 @@ int launch_bwd_td(const KArgs& a, bool causal, bool dropout, bool sparse, hipStr
     aq.chunk = (aq.n_items + kXcds - 1) / kXcds;
   }
   const dim3 grid_q(kXcds * aq.chunk);
-  // ATTN_DKV_VARIANT=base selects the single-role dK/dV kernel of this file instead of the
-  // role-split one (bench-time comparison)
-  static const bool dkv_base = [] {
-    const char* v = getenv("ATTN_DKV_VARIANT");
-    return v != nullptr && v[0] == 'b';
-  }();
 #define ATTN_BWD_CASE(C, P, S)                                                   \
   if (causal == C && dropout == P && sparse == S) {                              \
     hipLaunchKernelGGL((dq_kernel<T, D, C, P, S>), grid_q, block, 0, s, aq);     \
     e = (int)hipGetLastError();                                                  \
     if (e != 0) return e;                                                        \
     if (ev) (void)hipEventRecord(ev[2], s);                                      \
-    if (dkv_base) {                                                              \
-      hipLaunchKernelGGL((dkv_kernel<T, D, C, P, S>), grid, block, 0, s, a);     \
-      e = (int)hipGetLastError();                                                \
-    } else {                                                                     \
-      e = launch_dkv_rs(a, kDtype<T>, D, C, P, S, s);                            \
-    }                                                                            \
+    e = launch_dkv_rs(a, kDtype<T>, D, C, P, S, s);                              \
     if (ev) (void)hipEventRecord(ev[3], s);                                      \
     return e;                                                                    \
   }

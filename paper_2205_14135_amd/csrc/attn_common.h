@@ -38,7 +38,7 @@ struct KArgs {
   float tau;               // softmax scale
   float scale_log2;        // tau * log2(e)
   float keep_scale;        // 1 / (1 - p_drop)
-  uint32_t drop_thr;       // keep iff philox word >= drop_thr
+  uint32_t drop_thr;       // keep iff 16-bit philox field >= drop_thr
   uint32_t seed_lo, seed_hi, offset_lo;
   int o_fp32;
   int n_items;             // work items (B*H*tiles)
@@ -92,6 +92,20 @@ __device__ __forceinline__ u32x4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_
   return r;
 }
 
+// Dropout draw (see the contract in include/attn.h): one Philox call decides the eight keys
+// 8 g8 .. 8 g8 + 7 of query row i; bit f of the result is set iff key 8 g8 + f is KEPT.
+__device__ __forceinline__ uint32_t philox_keep8(uint32_t g8, uint32_t i, uint32_t bh, uint32_t offset_lo,
+                                                uint32_t seed_lo, uint32_t seed_hi, uint32_t thr16) {
+  const u32x4 w = philox4x32_10(g8, i, bh, offset_lo, seed_lo, seed_hi);
+  uint32_t m = 0;
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    m |= ((w[t] & 0xFFFFu) >= thr16 ? 1u : 0u) << (2 * t);
+    m |= ((w[t] >> 16) >= thr16 ? 1u : 0u) << (2 * t + 1);
+  }
+  return m;
+}
+
 // value of the lane 32 positions away (wave64)
 __device__ __forceinline__ float xchg32(float x) {
   const uint32_t u = __builtin_bit_cast(uint32_t, x);
@@ -99,6 +113,27 @@ __device__ __forceinline__ float xchg32(float x) {
   // r[0] = {lo half, lo half}, r[1] = {hi half, hi half}
   const uint32_t other = (threadIdx.x & 32) ? r[0] : r[1];
   return __builtin_bit_cast(float, other);
+}
+
+// Keep bits of a 64-key tile in the "lane = query" layout (forward, dQ).  The two lanes of a
+// query (g = 0 / 1) need the same eight draws (key groups k0/8 .. k0/8 + 7) and different halves
+// of each: lane g draws the groups with i4 % 2 == g and the pair swaps the result words.
+// Returns {even, odd}: the draws of the groups with even / odd i4, already shifted so that the bit
+// of element (kb, i4, e) of THIS lane is bit 8 (2 kb + i4 / 2) + e of word i4 % 2.
+struct KeepLQ { uint32_t even, odd; };
+__device__ __forceinline__ KeepLQ keep_tile_lane_query(int k0, int qi, int bh, int g, uint32_t offset_lo,
+                                                       uint32_t seed_lo, uint32_t seed_hi, uint32_t thr16) {
+  uint32_t mine = 0;
+#pragma unroll
+  for (int n = 0; n < 4; ++n) {   // n = 2 kb + i4 / 2, with i4 = 2 (n % 2) + g
+    const uint32_t g8 = (uint32_t)(k0 >> 3) + 4 * (n >> 1) + 2 * (n & 1) + g;
+    mine |= philox_keep8(g8, (uint32_t)qi, (uint32_t)bh, offset_lo, seed_lo, seed_hi, thr16) << (8 * n);
+  }
+  const uint32_t theirs = __builtin_bit_cast(uint32_t, xchg32(__builtin_bit_cast(float, mine)));
+  KeepLQ k;
+  k.even = (g == 0 ? mine : theirs) >> (4 * g);
+  k.odd = (g == 1 ? mine : theirs) >> (4 * g);
+  return k;
 }
 
 // Work-item index for this workgroup: consecutive items share an XCD (workgroups are

@@ -183,16 +183,14 @@ __global__ __launch_bounds__(NT, 2) void fwd_kernel(const KArgs a) {
       l_run += psum;
       // ---- dropout on the unnormalised probabilities (the row sum above is undropped)
       if constexpr (DROPOUT) {
+        const KeepLQ kq = keep_tile_lane_query(k0, qi, bh, g, a.offset_lo, a.seed_lo, a.seed_hi, a.drop_thr);
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-          for (int i4 = 0; i4 < 4; ++i4) {
-            const uint32_t jg = (uint32_t)(k0 + 32 * kb + 8 * i4 + 4 * g) >> 2;
-            const u32x4 w = philox4x32_10(jg, (uint32_t)qi, (uint32_t)bh, a.offset_lo, a.seed_lo, a.seed_hi);
+          for (int i4 = 0; i4 < 4; ++i4)
 #pragma unroll
             for (int e = 0; e < 4; ++e)
-              if (w[e] < a.drop_thr) s[kb][4 * i4 + e] = 0.f;
-          }
+              if ((((i4 & 1) ? kq.odd : kq.even) >> (8 * (2 * kb + (i4 >> 1)) + e) & 1u) == 0) s[kb][4 * i4 + e] = 0.f;
       }
       // ---- P^T fragments (B operand): 16-key chunk cc = 2 kb + half
       T8 pf[4];
@@ -265,20 +263,24 @@ int launch_fwd_td(const KArgs& a, bool causal, bool dropout, bool sparse, hipStr
   return (int)hipErrorInvalidValue;
 }
 
-// keep[bh][i][j] for the test hook: one thread per group of four consecutive keys
+// keep[bh][i][j] for the test hook: one thread per group of eight consecutive keys
 __global__ void dropout_mask_kernel(const KArgs a, uint8_t* keep) {
-  const int64_t ngrp = (int64_t)a.N / 4;
+  const int64_t ngrp = (int64_t)a.N / 8;
   const int64_t total = (int64_t)a.B * a.H * a.N * ngrp;
   for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
        idx += (int64_t)gridDim.x * blockDim.x) {
-    const uint32_t jg = (uint32_t)(idx % ngrp);
+    const uint32_t g8 = (uint32_t)(idx % ngrp);
     const uint32_t i = (uint32_t)((idx / ngrp) % a.N);
     const uint32_t bh = (uint32_t)(idx / (ngrp * a.N));
-    const u32x4 w = philox4x32_10(jg, i, bh, a.offset_lo, a.seed_lo, a.seed_hi);
-    uint32_t packed = 0;
+    const uint32_t m = philox_keep8(g8, i, bh, a.offset_lo, a.seed_lo, a.seed_hi, a.drop_thr);
+    uint32_t lo = 0, hi = 0;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) packed |= (w[e] >= a.drop_thr ? 1u : 0u) << (8 * e);
-    *(uint32_t*)(keep + idx * 4) = packed;
+    for (int f = 0; f < 4; ++f) {
+      lo |= ((m >> f) & 1u) << (8 * f);
+      hi |= ((m >> (4 + f)) & 1u) << (8 * f);
+    }
+    *(uint32_t*)(keep + idx * 8) = lo;
+    *(uint32_t*)(keep + idx * 8 + 4) = hi;
   }
 }
 
@@ -294,8 +296,7 @@ int launch_fwd(const KArgs& a, int dtype, int d, bool causal, bool dropout, bool
     return v != nullptr ? v[0] : 'a';
   }();
   bool use_pp;
-  if (dropout) use_pp = d == 128;
-  else if (d == 128) use_pp = a.N >= 512;
+  if (d == 128) use_pp = dropout || a.N >= 512;
   else use_pp = a.N >= (causal ? 1024 : 2048);
   if (variant == 'b') use_pp = false;
   if (variant == 'p') use_pp = true;
@@ -308,7 +309,7 @@ int launch_fwd(const KArgs& a, int dtype, int d, bool causal, bool dropout, bool
 }
 
 int launch_dropout_mask(const KArgs& a, uint8_t* keep, hipStream_t s) {
-  const int64_t total = (int64_t)a.B * a.H * a.N * (a.N / 4);
+  const int64_t total = (int64_t)a.B * a.H * a.N * (a.N / 8);
   const int blocks = (int)((total + 255) / 256 < 65536 ? (total + 255) / 256 : 65536);
   hipLaunchKernelGGL(dropout_mask_kernel, dim3(blocks), dim3(256), 0, s, a, keep);
   return (int)hipGetLastError();

@@ -183,16 +183,14 @@ __device__ __forceinline__ void fwd_pp_rows(const KArgs& a, const int bh, const 
       }
     l_run += psum;
     if constexpr (DROPOUT) {
+      const KeepLQ kq = keep_tile_lane_query(k0, qi, bh, g, a.offset_lo, a.seed_lo, a.seed_hi, a.drop_thr);
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int i4 = 0; i4 < 4; ++i4) {
-          const uint32_t jg = (uint32_t)(k0 + 32 * kb + 8 * i4 + 4 * g) >> 2;
-          const u32x4 w = philox4x32_10(jg, (uint32_t)qi, (uint32_t)bh, a.offset_lo, a.seed_lo, a.seed_hi);
+        for (int i4 = 0; i4 < 4; ++i4)
 #pragma unroll
           for (int e = 0; e < 4; ++e)
-            if (w[e] < a.drop_thr) s[kb][4 * i4 + e] = 0.f;
-        }
+            if ((((i4 & 1) ? kq.odd : kq.even) >> (8 * (2 * kb + (i4 >> 1)) + e) & 1u) == 0) s[kb][4 * i4 + e] = 0.f;
     }
 #pragma unroll
     for (int cc = 0; cc < 4; ++cc)
