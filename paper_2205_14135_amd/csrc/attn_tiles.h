@@ -73,8 +73,12 @@ __device__ __forceinline__ void async_copy_b128(const void* gptr_lane, uint32_t 
 // byte offset: no vector ALU work when only the base changes from tile to tile.
 __device__ __forceinline__ void async_copy_b128(const void* gbase_uniform, uint32_t byte_off_lane, uint32_t lds_byte_addr) {
 #if defined(__HIP_DEVICE_COMPILE__)
+  // the base must sit in scalar registers whatever the compiler's divergence analysis thinks of it
+  const uint64_t bits = (uint64_t)(uintptr_t)gbase_uniform;
+  const uint64_t base = (uint64_t)__builtin_amdgcn_readfirstlane((uint32_t)bits) |
+                        ((uint64_t)__builtin_amdgcn_readfirstlane((uint32_t)(bits >> 32)) << 32);
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-               :: "s"(lds_byte_addr), "v"(byte_off_lane), "s"(gbase_uniform) : "memory");
+               :: "s"(lds_byte_addr), "v"(byte_off_lane), "s"(base) : "memory");
 #else
   (void)gbase_uniform; (void)byte_off_lane; (void)lds_byte_addr;
 #endif
