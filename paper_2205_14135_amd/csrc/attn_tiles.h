@@ -75,8 +75,10 @@ __device__ __forceinline__ void async_copy_b128(const void* gbase_uniform, uint3
 #if defined(__HIP_DEVICE_COMPILE__)
   // the base must sit in scalar registers whatever the compiler's divergence analysis thinks of it
   const uint64_t bits = (uint64_t)(uintptr_t)gbase_uniform;
-  const uint64_t base = (uint64_t)__builtin_amdgcn_readfirstlane((uint32_t)bits) |
-                        ((uint64_t)__builtin_amdgcn_readfirstlane((uint32_t)(bits >> 32)) << 32);
+  // (readfirstlane returns a signed int: widen through uint32_t, or bit 31 of the low word smears
+  // over the high word)
+  const uint64_t base = (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)bits) |
+                        ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(bits >> 32)) << 32);
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                :: "s"(lds_byte_addr), "v"(byte_off_lane), "s"(base) : "memory");
 #else
