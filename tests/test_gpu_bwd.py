@@ -63,3 +63,13 @@ def test_workspace_is_linear_in_n():
         sizes.append(binding.attn_bwd_workspace_bytes(binding.make_params(q, 0.125)))
     assert sizes[1] == 8 * sizes[0] and sizes[2] == 8 * sizes[1]
     assert sizes[0] <= 2 * 4 * 128 * 64 * 2
+
+
+@pytest.mark.parametrize("N,d", [(640, 128), (1152, 64), (896, 64)])
+def test_causal_paired_blocks_odd_count(N, d):
+    """Causal backward where work items pair a light and a heavy block (key blocks in the dK/dV
+    kernel, row blocks in the dQ kernel at d = 64), with an odd number of 128-token blocks."""
+    t, dev = hp.make_case(1, 3, N, d, "bf16", 950 + N + d)
+    res = hp.check_backward(t, dev, "bf16", 1 / math.sqrt(d), causal=True)
+    print("causal pairs bwd", N, d, res)
+    hp.assert_backward_ok(res)

@@ -84,3 +84,13 @@ def test_prefix_property():
         sub_d = {k: v[:, :, :n].contiguous() for k, v in dev.items()}
         res = hp.check_forward(sub_t, sub_d, "bf16", 0.125)
         hp.assert_forward_ok(res)
+
+
+@pytest.mark.parametrize("N,d", [(640, 128), (1152, 64), (1280, 128)])
+def test_causal_paired_row_blocks_odd_count(N, d):
+    """Causal problems in the two-group kernel, where a work item is a pair of 256-row blocks: an odd
+    number of blocks (the middle one stands alone) and a last block of only 128 valid rows."""
+    t, dev = hp.make_case(1, 3, N, d, "bf16", 900 + N + d)
+    res = hp.check_forward(t, dev, "bf16", 1 / math.sqrt(d), causal=True)
+    print("causal pairs fwd", N, d, res)
+    hp.assert_forward_ok(res)

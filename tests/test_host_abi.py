@@ -68,6 +68,7 @@ def test_struct_layout_matches_c():
     (dict(B=0), -2),
     (dict(stride_b=8192, stride_h=8192, stride_n=60), -2),
     (dict(stride_b=8192, stride_h=8192, stride_n=68), -2),
+    (dict(stride_b=1 << 40, stride_h=1 << 36, stride_n=(1 << 23) + 8), -2),   # rows too far apart for the tile copies
     (dict(dropout_p=1.0), -5),
     (dict(dropout_p=-0.1), -5),
     (dict(dropout_p=float("nan")), -5),
