@@ -81,8 +81,20 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const KArgs a) {
   // not have).
   constexpr bool PAIRED = CAUSAL && !SPARSE && D == 64;
   const int n_per_head = PAIRED ? (n_qt + 1) / 2 : n_qt;
-  const int bh = item / n_per_head;
-  const int q_item = item % n_per_head;
+  int bh = item / n_per_head;
+  int q_item = item % n_per_head;
+  if constexpr (CAUSAL && !PAIRED) {
+    // unpaired causal items: the row blocks of a.group consecutive heads are dealt out together,
+    // heaviest first, so that the items a compute unit receives last are light ones.  The host
+    // sizes the group so that the K and V of its heads (the L2 working set of an XCD) stay within
+    // 8 MiB: larger groups balance better but thrash L2 on long sequences.
+    const int n_heads = a.B * a.H;
+    const int grp0 = (bh / a.group) * a.group;             // first head of this group
+    const int gsz = min(a.group, n_heads - grp0);          // heads in it (the last group may be short)
+    const int within = (bh - grp0) * n_qt + q_item;        // position inside the group's items
+    bh = grp0 + within % gsz;
+    q_item = within / gsz;                                 // q_item-th heaviest block (see qt below)
+  }
   const int n_pass = PAIRED && q_item != n_qt - 1 - q_item ? 2 : 1;
 #pragma clang loop unroll(disable)
   for (int pass = 0; pass < n_pass; ++pass) {
@@ -263,6 +275,11 @@ int launch_bwd_td(const KArgs& a, bool causal, bool dropout, bool sparse, hipStr
   if (causal && !sparse && D == 64) {
     aq.n_items = a.B * a.H * ((a.N / 128 + 1) / 2);
     aq.chunk = (aq.n_items + kXcds - 1) / kXcds;
+  }
+  {
+    const int64_t kv_bytes = 2 * (int64_t)a.N * D * (int64_t)sizeof(T);
+    const int64_t fit = ((int64_t)8 << 20) / kv_bytes;
+    aq.group = (int)(fit < 1 ? 1 : (fit > 8 ? 8 : fit));
   }
   const dim3 grid_q(kXcds * aq.chunk);
 #define ATTN_BWD_CASE(C, P, S)                                                   \

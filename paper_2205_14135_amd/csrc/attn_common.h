@@ -43,6 +43,7 @@ struct KArgs {
   int o_fp32;
   int n_items;             // work items (B*H*tiles)
   int chunk;               // items per XCD = ceil(n_items / 8)
+  int group;               // causal dQ: heads whose row blocks are dealt out together, heaviest first
 };
 
 enum { kXcds = 8, kMaskBlock = 128 };
