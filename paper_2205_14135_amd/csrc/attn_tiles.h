@@ -1,28 +1,9 @@
-// Tile helpers shared by the backward kernels: staging of [64][D] tiles into swizzled LDS,
-// transposing-read offsets, fragment reads and the transposed accumulator store.
+// Tile helpers shared by the tile kernels: asynchronous copies of [64][D] tiles into swizzled
+// LDS, transposing-read offsets, fragment reads and the transposed accumulator store.
 #pragma once
 #include "attn_common.h"
 
 namespace attn {
-
-// Stages a [64][D] tile: global -> registers -> swizzled LDS.
-template <typename T, int D, int NT> struct TileStage {
-  typedef typename Vec<T>::x8 T8;
-  static constexpr int TILE = 64;
-  static constexpr int CPR = D / 8, RPP = NT / CPR, NP = TILE / RPP;
-  T8 reg[NP];
-  __device__ __forceinline__ void load(const T* g, int64_t sn, int row0) {
-    const int lrow = threadIdx.x / CPR, lchunk = threadIdx.x % CPR;
-#pragma unroll
-    for (int p = 0; p < NP; ++p)
-      reg[p] = *(const T8*)(g + (int64_t)(row0 + p * RPP + lrow) * sn + 8 * lchunk);
-  }
-  __device__ __forceinline__ void store(T* lds) const {
-    const int lrow = threadIdx.x / CPR, lchunk = threadIdx.x % CPR;
-#pragma unroll
-    for (int p = 0; p < NP; ++p) *(T8*)(lds + lds_off<D>(p * RPP + lrow, lchunk)) = reg[p];
-  }
-};
 
 // Asynchronous copy of a [64][D] tile from global memory straight into swizzled LDS (no register
 // staging, no LDS store instructions): each global_load_lds_dwordx4 moves 64 lanes x 16 bytes to
