@@ -26,26 +26,16 @@ constexpr int BR = 128;  // query rows per workgroup
 constexpr int BC = 64;   // keys per K/V tile
 constexpr int NT = 256;  // threads
 
-template <int D> struct Lds {
-  static constexpr int KS = D + 8;    // K row stride (elements): 16-byte row skew, conflict-free b128 reads
-  static constexpr int VS = D + 32;   // V row stride: consecutive rows 16 banks apart for the transposing read
-  static constexpr int K_ELEMS = BC * KS;
-  static constexpr int V_ELEMS = BC * VS;
-};
-
 template <typename T, int D, bool CAUSAL, bool DROPOUT, bool SPARSE>
 __global__ __launch_bounds__(NT, 2) void fwd_kernel(const KArgs a) {
   typedef typename Vec<T>::x8 T8;
   typedef typename Vec<T>::x4 T4;
-  typedef Lds<D> L;
   constexpr int KK = D / 16;        // MFMA k-steps over the head dimension
   constexpr int DB = D / 32;        // 32-row blocks of O^T
-  constexpr int CPR = D / 8;        // 16-byte chunks per row
-  constexpr int RPP = NT / CPR;     // rows per load pass
-  constexpr int NP = BC / RPP;      // load passes per tile
 
-  __shared__ __attribute__((aligned(16))) T Ks[L::K_ELEMS];
-  __shared__ __attribute__((aligned(16))) T Vs[L::V_ELEMS];
+  // double buffered, unpadded XOR-swizzled tiles, filled by asynchronous global-to-LDS copies
+  __shared__ __attribute__((aligned(16))) T Ks[2][BC * D];
+  __shared__ __attribute__((aligned(16))) T Vs[2][BC * D];
 
   const int item = xcd_item(a.n_items, a.chunk);
   if (item < 0) return;
@@ -90,54 +80,54 @@ __global__ __launch_bounds__(NT, 2) void fwd_kernel(const KArgs a) {
     it.init(SPARSE ? a.mask + (int64_t)h * a.mask_sh + (int64_t)qt * a.T : nullptr, 1, 0, lim);
   }
 
-  // global -> register staging of one K/V tile
-  const int lrow = tid / CPR, lchunk = tid % CPR;
-  T8 kreg[NP], vreg[NP];
-  auto gload = [&](int jt) {
-#pragma unroll
-    for (int p = 0; p < NP; ++p) {
-      const int64_t off = (int64_t)(jt * BC + p * RPP + lrow) * a.sn + 8 * lchunk;
-      kreg[p] = *(const T8*)(Kg + off);
-      vreg[p] = *(const T8*)(Vg + off);
-    }
-  };
-  auto sstore = [&]() {
-#pragma unroll
-    for (int p = 0; p < NP; ++p) {
-      *(T8*)(Ks + (p * RPP + lrow) * L::KS + 8 * lchunk) = kreg[p];
-      *(T8*)(Vs + (p * RPP + lrow) * L::VS + 8 * lchunk) = vreg[p];
-    }
-  };
-
-  // transposing-read address pattern: 16-lane group q16 covers d columns 16 (q16 & 1) .. +15 of
-  // a 32-row d block, lanes 4t+j of the group point at key row t, columns 4j .. 4j+3
-  const int i16 = lane & 15, q16 = lane >> 4;
-  const int v_lane_off = (4 * g + (i16 >> 2)) * L::VS + 16 * (q16 & 1) + 4 * (i16 & 3);
+  TrOffsets<D> tro;
+  tro.init();
+  TileAsync<T, D, NT / 64> dma;
+  dma.init(a.sn, wave);
 
   const float c = a.scale_log2;
   int jt = it.next();
-  if (jt >= 0) gload(jt);
+  int buf = 0;
+  if (jt >= 0) {
+    dma.copy(Kg + (int64_t)jt * BC * a.sn, Ks[0]);
+    dma.copy(Vg + (int64_t)jt * BC * a.sn, Vs[0]);
+  }
+  wait_async_copies();
+  __syncthreads();   // tile 0 has landed, and so have the Q fragments
   while (jt >= 0) {
-    sstore();
-    __syncthreads();
     const int jn = it.next();
-    if (jn >= 0) gload(jn);
+    if (jn >= 0) {   // the next tile streams into the other buffer while this one is used
+      dma.copy(Kg + (int64_t)jn * BC * a.sn, Ks[buf ^ 1]);
+      dma.copy(Vg + (int64_t)jn * BC * a.sn, Vs[buf ^ 1]);
+    }
+    const T* Kt = Ks[buf];
+    const T* Vt = Vs[buf];
 
     const int k0 = jt * BC;
     const bool wave_active = !CAUSAL || k0 <= q0 + 31;
     if (wave_active) {
-      // ---- S^T = K Q^T  (64 keys x 32 queries per wavefront)
+      // ---- S^T = K Q^T  (64 keys x 32 queries per wavefront); operand reads run PF fragments
+      // ahead of their MFMA (the scheduling barriers keep that distance)
+      constexpr int PF = 4;
       f32x16 s[2];
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) s[kb][i] = 0.f;
+      {
+        auto k_frag = [&](int f) {   // f = 2 kk + kb
+          return *(const T8*)(Kt + lds_off<D>(32 * (f & 1) + r, 2 * (f >> 1) + g));
+        };
+        T8 ring[PF];
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
+        for (int f = 0; f < PF; ++f) ring[f] = k_frag(f);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-          const T8 kf = *(const T8*)(Ks + (32 * kb + r) * L::KS + 16 * kk + 8 * g);
-          s[kb] = mfma32(kf, qf[kk], s[kb]);
+        for (int f = 0; f < 2 * KK; ++f) {
+          const T8 cur = ring[f % PF];
+          s[f & 1] = mfma32(cur, qf[f >> 1], s[f & 1]);
+          if (f + PF < 2 * KK) ring[f % PF] = k_frag(f + PF);
+          __builtin_amdgcn_sched_barrier(0);
         }
       }
       // ---- causal mask on tiles that cross the diagonal, padding mask on the last tile
@@ -199,22 +189,28 @@ __global__ __launch_bounds__(NT, 2) void fwd_kernel(const KArgs a) {
 #pragma unroll
         for (int t = 0; t < 8; ++t) pf[cc][t] = (T)s[cc >> 1][8 * (cc & 1) + t];
       // ---- O^T += V^T P^T
+      {
+        auto v_frag = [&](int f) {   // f = DB cc + db: consecutive MFMAs hit different accumulators
+          const T* base = Vt + 16 * (f / DB) * D;
+          return tr_frag<T8>(base + tro.off[f % DB][0], base + tro.off[f % DB][1]);
+        };
+        T8 ring[PF];
 #pragma unroll
-      for (int db = 0; db < DB; ++db) {
+        for (int f = 0; f < PF; ++f) ring[f] = v_frag(f);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int cc = 0; cc < 4; ++cc) {
-          const T* vp = Vs + v_lane_off + (16 * cc) * L::VS + 32 * db;
-          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (__attribute__((address_space(3))) s16x4*)(vp));
-          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (__attribute__((address_space(3))) s16x4*)(vp + 8 * L::VS));
-          const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-          o[db] = mfma32(__builtin_bit_cast(T8, both), pf[cc], o[db]);
+        for (int f = 0; f < 4 * DB; ++f) {
+          const T8 cur = ring[f % PF];
+          o[f % DB] = mfma32(cur, pf[f / DB], o[f % DB]);
+          if (f + PF < 4 * DB) ring[f % PF] = v_frag(f + PF);
+          __builtin_amdgcn_sched_barrier(0);
         }
       }
     }
-    __syncthreads();
+    wait_async_copies();
+    __syncthreads();   // the next tile has landed, and everyone is done with this buffer
     jt = jn;
+    buf ^= 1;
   }
 
   // ---- epilogue: normalise, apply the dropout scale, write O and L once
@@ -238,7 +234,7 @@ __global__ __launch_bounds__(NT, 2) void fwd_kernel(const KArgs a) {
       }
   } else {
     // coalesced row stores through the (now idle) tile buffers: two wavefronts per buffer
-    T* stage = (wave < 2 ? Ks + wave * 32 * D : Vs + (wave - 2) * 32 * D);
+    T* stage = (wave < 2 ? &Ks[0][0] + wave * 32 * D : &Vs[0][0] + (wave - 2) * 32 * D);
     store_rows_coalesced<T, D>(stage, (T*)a.O + head_off + (int64_t)q0 * a.sn, a.sn, o, inv);
   }
 }
