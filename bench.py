@@ -150,10 +150,8 @@ def run_gpu(cfg, steps, warmup, seed, mask_override=None):
     # choice mirrors launch_fwd() in csrc/attn_fwd.hip)
     if cfg["sparse"]:
         use_pp = False
-    elif d == 128:
-        use_pp = cfg["p"] > 0 or N >= 512
     else:
-        use_pp = N >= (1024 if cfg["causal"] else 2048)
+        use_pp = d == 128 and (cfg["p"] > 0 or N >= 512)
     names = ["fwd_pp_kernel" if use_pp else "fwd_kernel", "rowdot_kernel", "dq_kernel", "dkv_rs_kernel"]
     dur = {n: 0.0 for n in names}
     for e in evs:

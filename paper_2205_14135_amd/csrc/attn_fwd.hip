@@ -40,9 +40,18 @@ __global__ __launch_bounds__(NT, 2) void fwd_kernel(const KArgs a) {
   const int item = xcd_item(a.n_items, a.chunk);
   if (item < 0) return;
   const int n_qt = a.N / BR;
-  const int bh = item / n_qt;
-  // heavy (late) tiles first under a causal mask
-  const int qt = CAUSAL ? (n_qt - 1 - item % n_qt) : item % n_qt;
+  // Work item = (head, row block), heavy (late) blocks first under a causal mask.  For dense
+  // causal d = 64 problems an item is the pair (n_qt - 1 - q, q), one block per pass, so that
+  // every workgroup does the same amount of work.
+  constexpr bool PAIRED = CAUSAL && !SPARSE && D == 64;
+  const int n_per_head = PAIRED ? (n_qt + 1) / 2 : n_qt;
+  const int bh = item / n_per_head;
+  const int q_item = item % n_per_head;
+  const int n_pass = PAIRED && q_item != n_qt - 1 - q_item ? 2 : 1;
+#pragma clang loop unroll(disable)
+  for (int pass = 0; pass < n_pass; ++pass) {
+  if (pass) __syncthreads();   // the tile buffers staged the first block's output rows
+  const int qt = PAIRED ? (pass ? q_item : n_qt - 1 - q_item) : (CAUSAL ? n_qt - 1 - q_item : q_item);
   const int b = bh / a.H, h = bh % a.H;
   const int64_t head_off = (int64_t)b * a.sb + (int64_t)h * a.sh;
   const T* __restrict__ Qg = (const T*)a.Q + head_off;
@@ -237,10 +246,16 @@ __global__ __launch_bounds__(NT, 2) void fwd_kernel(const KArgs a) {
     T* stage = (wave < 2 ? &Ks[0][0] + wave * 32 * D : &Vs[0][0] + (wave - 2) * 32 * D);
     store_rows_coalesced<T, D>(stage, (T*)a.O + head_off + (int64_t)q0 * a.sn, a.sn, o, inv);
   }
+  }  // for pass
 }
 
 template <typename T, int D>
-int launch_fwd_td(const KArgs& a, bool causal, bool dropout, bool sparse, hipStream_t s) {
+int launch_fwd_td(const KArgs& a_in, bool causal, bool dropout, bool sparse, hipStream_t s) {
+  KArgs a = a_in;
+  if (causal && !sparse && D == 64) {   // items are pairs of row blocks
+    a.n_items = a.B * a.H * ((a.N / BR + 1) / 2);
+    a.chunk = (a.n_items + kXcds - 1) / kXcds;
+  }
   const dim3 grid(kXcds * a.chunk), block(NT);
 #define ATTN_FWD_CASE(C, P, S)                                                         \
   if (causal == C && dropout == P && sparse == S) {                                    \
@@ -283,17 +298,16 @@ __global__ void dropout_mask_kernel(const KArgs a, uint8_t* keep) {
 }  // namespace
 
 int launch_fwd(const KArgs& a, int dtype, int d, bool causal, bool dropout, bool sparse, hipStream_t s) {
-  // Dense problems take the ping-pong kernel (attn_fwd_pp.hip) where it measured faster on
-  // MI355X: long sequences, where its 256-row workgroups still fill the chip and the MFMA /
-  // softmax overlap pays; short ones keep the 4-wavefront kernel of this file, and so do all
-  // block-sparse problems.  ATTN_FWD_VARIANT=base|pp overrides the choice (bench-time comparison).
+  // Dense d = 128 problems take the two-group ping-pong kernel (attn_fwd_pp.hip) from N = 512 on
+  // (and always with dropout): there the matrix blocks are long enough for the MFMA / softmax
+  // overlap to pay.  At d = 64 the vector ALU work dominates and two free-running workgroups
+  // per compute unit (this file) measured faster at every N; block-sparse problems always take
+  // this kernel.  ATTN_FWD_VARIANT=base|pp overrides the choice (bench-time comparison).
   static const char variant = [] {
     const char* v = getenv("ATTN_FWD_VARIANT");
     return v != nullptr ? v[0] : 'a';
   }();
-  bool use_pp;
-  if (d == 128) use_pp = dropout || a.N >= 512;
-  else use_pp = a.N >= (causal ? 1024 : 2048);
+  bool use_pp = d == 128 && (dropout || a.N >= 512);
   if (variant == 'b') use_pp = false;
   if (variant == 'p') use_pp = true;
   if (!sparse && use_pp) return launch_fwd_pp(a, dtype, d, causal, dropout, s);
