@@ -24,7 +24,7 @@ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 int check_params(const attn_params* p, Checked* out) {
   if (p == nullptr) return ATTN_ERR_NULL;
   if (p->dtype != ATTN_FP16 && p->dtype != ATTN_BF16) return ATTN_ERR_DTYPE;
-  if (p->d != 64 && p->d != 128) return ATTN_ERR_HEADDIM;
+  if (p->d != 32 && p->d != 64 && p->d != 128) return ATTN_ERR_HEADDIM;
   if (p->B <= 0 || p->H <= 0 || p->N <= 0) return ATTN_ERR_SHAPE;
   if (p->N % attn::kMaskBlock != 0) return ATTN_ERR_SHAPE;
   if ((int64_t)p->B * p->H > (int64_t)1 << 24) return ATTN_ERR_SHAPE;
@@ -218,7 +218,7 @@ const char* attn_strerror(int status) {
     case ATTN_ERR_NULL: return "a required pointer is NULL";
     case ATTN_ERR_SHAPE: return "unsupported shape or strides (N must be a positive multiple of 128)";
     case ATTN_ERR_DTYPE: return "dtype must be ATTN_FP16 or ATTN_BF16";
-    case ATTN_ERR_HEADDIM: return "head dimension must be 64 or 128";
+    case ATTN_ERR_HEADDIM: return "head dimension must be 32, 64 or 128";
     case ATTN_ERR_DROPOUT_P: return "dropout_p must be in [0, 1)";
     case ATTN_ERR_SCALE: return "softmax_scale must be finite and positive";
     case ATTN_ERR_WORKSPACE: return "workspace is NULL, not 256-byte aligned, or too small";

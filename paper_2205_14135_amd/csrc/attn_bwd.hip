@@ -308,6 +308,8 @@ int launch_bwd_td(const KArgs& a, bool causal, bool dropout, bool sparse, hipStr
 
 int launch_bwd(const KArgs& a, int dtype, int d, bool causal, bool dropout, bool sparse, hipStream_t s,
                hipEvent_t* ev) {
+  if (dtype == 0 && d == 32) return launch_bwd_td<_Float16, 32>(a, causal, dropout, sparse, s, ev);
+  if (dtype == 1 && d == 32) return launch_bwd_td<__bf16, 32>(a, causal, dropout, sparse, s, ev);
   if (dtype == 0 && d == 64) return launch_bwd_td<_Float16, 64>(a, causal, dropout, sparse, s, ev);
   if (dtype == 0 && d == 128) return launch_bwd_td<_Float16, 128>(a, causal, dropout, sparse, s, ev);
   if (dtype == 1 && d == 64) return launch_bwd_td<__bf16, 64>(a, causal, dropout, sparse, s, ev);

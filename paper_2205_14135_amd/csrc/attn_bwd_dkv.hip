@@ -468,6 +468,8 @@ int launch_td(KArgs a, bool causal, bool dropout, bool sparse, hipStream_t s) {
 }  // namespace
 
 int launch_dkv_rs(const KArgs& a, int dtype, int d, bool causal, bool dropout, bool sparse, hipStream_t s) {
+  if (dtype == 0 && d == 32) return launch_td<_Float16, 32>(a, causal, dropout, sparse, s);
+  if (dtype == 1 && d == 32) return launch_td<__bf16, 32>(a, causal, dropout, sparse, s);
   if (dtype == 0 && d == 64) return launch_td<_Float16, 64>(a, causal, dropout, sparse, s);
   if (dtype == 0 && d == 128) return launch_td<_Float16, 128>(a, causal, dropout, sparse, s);
   if (dtype == 1 && d == 64) return launch_td<__bf16, 64>(a, causal, dropout, sparse, s);

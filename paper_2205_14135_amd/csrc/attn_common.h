@@ -149,7 +149,8 @@ __device__ __forceinline__ int xcd_item(int n_items, int chunk) {
 // chunk (row-wise 16-byte operand reads) and 4 consecutive rows x 64 bytes (transposing reads).
 template <int D> __device__ __forceinline__ int swz_bits(int row) {
   if constexpr (D == 128) return ((row & 3) << 2) | ((row >> 2) & 3);
-  else return (((row >> 1) & 1) << 2) | ((row >> 2) & 3);
+  else if constexpr (D == 64) return (((row >> 1) & 1) << 2) | ((row >> 2) & 3);
+  else return (row >> 2) & 3;   // D == 32: four chunks per row, four rows per 256 bytes
 }
 template <int D> __device__ __forceinline__ int lds_off(int row, int chunk) {
   return row * D + ((chunk ^ swz_bits<D>(row)) << 3);

@@ -309,8 +309,10 @@ int launch_fwd(const KArgs& a, int dtype, int d, bool causal, bool dropout, bool
   }();
   bool use_pp = d == 128 && (dropout || a.N >= 512);
   if (variant == 'b') use_pp = false;
-  if (variant == 'p') use_pp = true;
+  if (variant == 'p' && d != 32) use_pp = true;
   if (!sparse && use_pp) return launch_fwd_pp(a, dtype, d, causal, dropout, s);
+  if (dtype == 0 && d == 32) return launch_fwd_td<_Float16, 32>(a, causal, dropout, sparse, s);
+  if (dtype == 1 && d == 32) return launch_fwd_td<__bf16, 32>(a, causal, dropout, sparse, s);
   if (dtype == 0 && d == 64) return launch_fwd_td<_Float16, 64>(a, causal, dropout, sparse, s);
   if (dtype == 0 && d == 128) return launch_fwd_td<_Float16, 128>(a, causal, dropout, sparse, s);
   if (dtype == 1 && d == 64) return launch_fwd_td<__bf16, 64>(a, causal, dropout, sparse, s);
