@@ -27,6 +27,8 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_TFLOPS = {"bf16": 2500.0, "fp16": 2500.0}   # MI355X dense MFMA peak
+PEAK_HBM_GBPS = 8000.0
+ROTATING_SETS = 4      # separate copies of all tensors for the cache-cold timing (>= 1 GiB in total)
 
 
 def workloads():
@@ -93,7 +95,18 @@ def flops_fwd(cfg, nnz_blocks=None):
     return f * (0.5 if cfg["causal"] else 1.0)
 
 
-def run_gpu(cfg, steps, warmup, seed, mask_override=None):
+def io_bytes(cfg):
+    """Minimum HBM bytes of the forward and of the backward pass: every input read once, every
+    output written once (forward: Q, K, V in, O and the row statistic out; backward: Q, K, V, O, dO
+    and the row statistic in, dQ, dK, dV out)."""
+    rows = cfg["B"] * cfg["H"] * cfg["N"]
+    elem = rows * cfg["d"] * 2
+    return 4 * elem + 4 * rows, 8 * elem + 4 * rows
+
+
+def run_gpu(cfg, steps, warmup, seed, mask_override=None, nsets=1):
+    """Times `steps` forward+backward passes.  nsets > 1 rotates over that many separate copies of
+    all inputs and outputs, so that no step finds its tensors in the 256 MB last-level cache."""
     import numpy as np
     import torch
     from paper_2205_14135_amd import binding, inputs
@@ -102,7 +115,7 @@ def run_gpu(cfg, steps, warmup, seed, mask_override=None):
     torch.cuda.set_device(dev)
     B, H, N, d = cfg["B"], cfg["H"], cfg["N"], cfg["d"]
     t = inputs.gaussian_tensors(B, H, N, d, cfg["dtype"], seed)
-    g = {k: inputs.to_torch(v, cfg["dtype"], dev) for k, v in t.items()}
+    g0 = {k: inputs.to_torch(v, cfg["dtype"], dev) for k, v in t.items()}
     tau = 1.0 / math.sqrt(d)
     kw = dict(softmax_scale=tau, causal=cfg["causal"], dropout_p=cfg["p"],
               seed=inputs.BASE_DROPOUT_SEED, offset=0)
@@ -112,38 +125,44 @@ def run_gpu(cfg, steps, warmup, seed, mask_override=None):
         bm_np = inputs.butterfly_block_mask(N // 128) if mask_override is None else mask_override
         bm = torch.from_numpy(bm_np).to(dev)
         nnz = int(bm_np.sum())
-    O = torch.empty_like(g["Q"])
-    L = torch.empty((B, H, N), dtype=torch.float32, device=dev)
-    grads = tuple(torch.empty_like(g["Q"]) for _ in range(3))
-    pp = binding.make_params(g["Q"], tau)
+    sets = []
+    for i in range(nsets):
+        g = g0 if i == 0 else {k: v.clone() for k, v in g0.items()}
+        sets.append(dict(g=g, O=torch.empty_like(g["Q"]),
+                         L=torch.empty((B, H, N), dtype=torch.float32, device=dev),
+                         grads=tuple(torch.empty_like(g["Q"]) for _ in range(3))))
+    pp = binding.make_params(g0["Q"], tau)
     ws_bytes = binding.attn_blocksparse_bwd_workspace_bytes(pp) if cfg["sparse"] else binding.attn_bwd_workspace_bytes(pp)
     ws = torch.empty(max(256, ws_bytes), dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream(dev).cuda_stream
     hev = HipEvents()
 
-    def fwd():
+    def fwd(z):
+        g = z["g"]
         if bm is None:
-            binding.attn_fwd(g["Q"], g["K"], g["V"], out=O, lse=L, **kw)
+            binding.attn_fwd(g["Q"], g["K"], g["V"], out=z["O"], lse=z["L"], **kw)
         else:
-            binding.attn_blocksparse_fwd(g["Q"], g["K"], g["V"], bm, out=O, lse=L, **kw)
+            binding.attn_blocksparse_fwd(g["Q"], g["K"], g["V"], bm, out=z["O"], lse=z["L"], **kw)
 
-    def bwd(events):
-        binding.attn_bwd_timed(g["Q"], g["K"], g["V"], O, g["dO"], L, events, block_mask=bm,
-                               grads=grads, workspace=ws, **kw)
+    def bwd(z, events):
+        g = z["g"]
+        binding.attn_bwd_timed(g["Q"], g["K"], g["V"], z["O"], g["dO"], z["L"], events, block_mask=bm,
+                               grads=z["grads"], workspace=ws, **kw)
 
     scratch_ev = [hev.new() for _ in range(4)]
-    for _ in range(warmup):
-        fwd()
-        bwd(scratch_ev)
+    for i in range(max(warmup, nsets)):     # every set needs its O and row statistic before a backward
+        fwd(sets[i % nsets])
+        bwd(sets[i % nsets], scratch_ev)
     torch.cuda.synchronize()
     evs = [[hev.new() for _ in range(5)] for _ in range(steps)]   # f0, f1=b0, b1, b2, b3
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(steps):
         e = evs[s]
+        z = sets[s % nsets]
         hev.record(e[0], stream)
-        fwd()
-        bwd(e[1:5])
+        fwd(z)
+        bwd(z, e[1:5])
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
     # event intervals, labelled with the kernels the library launches for this workload (the forward
@@ -153,15 +172,42 @@ def run_gpu(cfg, steps, warmup, seed, mask_override=None):
     else:
         use_pp = d == 128 and (cfg["p"] > 0 or N >= 512)
     names = ["fwd_pp_kernel" if use_pp else "fwd_kernel", "rowdot_kernel", "dq_kernel", "dkv_rs_kernel"]
-    dur = {n: 0.0 for n in names}
+    per_step = {n: [] for n in names}
     for e in evs:
         for i, n in enumerate(names):
-            dur[n] += hev.elapsed_ms(e[i], e[i + 1])
-    dur = {n: v / steps for n, v in dur.items()}
+            per_step[n].append(hev.elapsed_ms(e[i], e[i + 1]))
+    dur = {n: sum(v) / steps for n, v in per_step.items()}
+    fwd_steps = np.array(per_step[names[0]])
+    bwd_steps = np.sum([per_step[n] for n in names[1:]], axis=0)
+    stats = dict(fwd_median=float(np.median(fwd_steps)), fwd_min=float(fwd_steps.min()),
+                 bwd_median=float(np.median(bwd_steps)), bwd_min=float(bwd_steps.min()))
     hev.close()
     peak_bytes = torch.cuda.max_memory_allocated(dev)
     return dict(ms_per_step=wall_ms / steps, kernel_ms=dur, names=names, nnz=nnz, tensors=t, block_mask=bm_np, tau=tau,
-                peak_bytes=peak_bytes)
+                peak_bytes=peak_bytes, stats=stats)
+
+
+def measured_mfma_rate(dtype):
+    """TFLOP/s of a kernel that only issues matrix instructions on register operands: what this
+    GPU sustains at the clock it holds under that load (the published peak assumes 2.4 GHz)."""
+    import torch
+    from paper_2205_14135_amd import binding
+    dev = torch.device("cuda:0")
+    sink = torch.zeros(64, dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream(dev).cuda_stream
+    hev = HipEvents()
+    binding.attn_debug_mfma_rate(dtype, 2000, sink)
+    torch.cuda.synchronize()
+    e = [hev.new() for _ in range(4)]
+    flops = 0.0
+    for i in range(3):
+        hev.record(e[i], stream)
+        flops = binding.attn_debug_mfma_rate(dtype, 20000, sink)
+    hev.record(e[3], stream)
+    torch.cuda.synchronize()
+    ms = hev.elapsed_ms(e[0], e[3]) / 3
+    hev.close()
+    return flops / ms * 1e-9
 
 
 def sparsity_sweep(steps):
@@ -346,23 +392,51 @@ def main():
         return
 
     if args.sweep:
+        sweep_steps = max(3, args.steps // 3)
         for name in sorted(wl):
             c = wl[name]
-            r = run_gpu(c, max(3, args.steps // 3), 2, inputs.BASE_SEED + 3)
+            r = run_gpu(c, sweep_steps, 2, inputs.BASE_SEED + 3)
             f = flops_fwd(c, r["nnz"])
+            nnz_blocks = r["nnz"]
             k = [r["kernel_ms"][n] for n in r["names"]]
             fwd_ms, bwd_ms = k[0], k[1] + k[2] + k[3]
-            print(json.dumps(dict(workload=name, fwd_ms=round(fwd_ms, 4), bwd_ms=round(bwd_ms, 4),
-                                  fwd_tflops=round(f / fwd_ms * 1e-9, 1),
-                                  bwd_tflops=round(2.5 * f / bwd_ms * 1e-9, 1),
-                                  fwd_bwd_tflops=round(3.5 * f / (fwd_ms + bwd_ms) * 1e-9, 1))),
-                  file=sys.stderr, flush=True)
+            by_f, by_b = io_bytes(c)
+            st = r["stats"]
+            del r
+            cold = run_gpu(c, sweep_steps, 2, inputs.BASE_SEED + 3, nsets=ROTATING_SETS)
+            ck = [cold["kernel_ms"][n] for n in cold["names"]]
+            del cold
+            line = dict(workload=name, fwd_ms=round(fwd_ms, 4), bwd_ms=round(bwd_ms, 4),
+                        fwd_tflops=round(f / fwd_ms * 1e-9, 1),
+                        bwd_tflops=round(2.5 * f / bwd_ms * 1e-9, 1),
+                        fwd_bwd_tflops=round(3.5 * f / (fwd_ms + bwd_ms) * 1e-9, 1),
+                        fwd_median_ms=round(st["fwd_median"], 4), fwd_min_ms=round(st["fwd_min"], 4),
+                        bwd_median_ms=round(st["bwd_median"], 4), bwd_min_ms=round(st["bwd_min"], 4),
+                        fwd_ms_rotating=round(ck[0], 4), bwd_ms_rotating=round(sum(ck[1:]), 4),
+                        fwd_min_GBps=round(by_f / fwd_ms * 1e-6, 1), bwd_min_GBps=round(by_b / bwd_ms * 1e-6, 1),
+                        fwd_hbm_frac=round(by_f / fwd_ms * 1e-6 / PEAK_HBM_GBPS, 4),
+                        bwd_hbm_frac=round(by_b / bwd_ms * 1e-6 / PEAK_HBM_GBPS, 4))
+            if c["sparse"]:
+                # the dense kernels on the same tensors: the paper's claim is a runtime that falls in
+                # proportion to the fraction of kept blocks (Section 3.3, Proposition 4)
+                dn = run_gpu(dict(c, sparse=False), 3, 1, inputs.BASE_SEED + 3)
+                dk = [dn["kernel_ms"][n] for n in dn["names"]]
+                del dn
+                T = c["N"] // 128
+                line.update(kept_fraction=round(nnz_blocks / (T * T), 5),
+                            dense_fwd_ms=round(dk[0], 4), dense_bwd_ms=round(sum(dk[1:]), 4),
+                            speedup_fwd=round(dk[0] / fwd_ms, 1), speedup_bwd=round(sum(dk[1:]) / bwd_ms, 1))
+            print(json.dumps(line), file=sys.stderr, flush=True)
 
     cfg = wl[args.workload]
     run = run_gpu(cfg, args.steps, args.warmup, inputs.BASE_SEED + 3)
     f_fwd = flops_fwd(cfg, run["nnz"])
     total = 3.5 * f_fwd
     value = total / run["ms_per_step"] * 1e-9
+    rot = run_gpu(cfg, args.steps, args.warmup, inputs.BASE_SEED + 3, nsets=ROTATING_SETS)
+    rot_ms = rot["ms_per_step"]
+    del rot
+    mfma_rate = measured_mfma_rate(cfg["dtype"])
     kms = run["kernel_ms"]
     # algorithmic FLOPs of each launch: forward two tile products; dK/dV kernel four of the five
     # backward products (S, dP, dV, dK); dQ kernel one (its S and dP are recomputation)
@@ -386,6 +460,12 @@ def main():
         "data": "synthetic",
         "config": {"workload": args.workload, **{k: cfg[k] for k in ("B", "H", "N", "d", "causal", "p", "sparse")}},
         "frac_of_mfma_peak": round(value / peak, 4),
+        "cache": "one set of tensors, reused every step (the value above)",
+        "rotating_buffers": {"sets": ROTATING_SETS, "ms_per_step": round(rot_ms, 4),
+                             "value": round(total / rot_ms * 1e-9, 2)},
+        "measured_mfma_rate": {"tflops": round(mfma_rate, 1), "frac_of_it": round(value / mfma_rate, 4),
+                               "what": "register-operand 32x32x16 MFMA loop on this GPU, same dtype"},
+        "step_stats_ms": {k: round(v, 4) for k, v in run["stats"].items()},
         "roofline": {
             "bound": "mfma", "kernel": dominant, "achieved": round(achieved, 2), "peak": peak,
             "unit": "TFLOP/s", "frac": round(achieved / peak, 4),

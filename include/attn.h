@@ -179,6 +179,17 @@ int attn_bwd_timed(const attn_params* p, const uint8_t* block_mask, int32_t mask
  */
 int attn_debug_dropout_mask(const attn_params* p, uint8_t* keep);
 
+/*
+ * Measurement aid, outside the paper's operation: launches on `stream` a kernel that
+ * only issues 32x32x16 matrix instructions of the given dtype on register operands
+ * (2048 workgroups of 4 wavefronts, 4 * iters instructions per wavefront), so a
+ * benchmark that times the launch can quote the matrix rate this GPU sustains under
+ * load next to the published peak.  sink: device pointer to at least one float, never
+ * written in practice; *flops (host pointer, may be NULL) receives the number of
+ * floating-point operations launched.  iters in [1, 2^20].  Asynchronous.
+ */
+int attn_debug_mfma_rate(int32_t dtype, int32_t iters, float* sink, void* stream, double* flops);
+
 /* Static, human-readable text for a status code. */
 const char* attn_strerror(int status);
 

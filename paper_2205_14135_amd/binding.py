@@ -19,7 +19,7 @@ ATTN_FP16, ATTN_BF16 = 0, 1
 
 SYMBOLS = (
     "attn_fwd", "attn_bwd_workspace_bytes", "attn_blocksparse_bwd_workspace_bytes", "attn_bwd", "attn_blocksparse_fwd",
-    "attn_blocksparse_bwd", "attn_bwd_timed", "attn_debug_dropout_mask", "attn_strerror",
+    "attn_blocksparse_bwd", "attn_bwd_timed", "attn_debug_dropout_mask", "attn_debug_mfma_rate", "attn_strerror",
     "attn_version",
 )
 
@@ -76,6 +76,8 @@ def load() -> ctypes.CDLL:
     lib.attn_bwd_timed.restype = ctypes.c_int
     lib.attn_debug_dropout_mask.argtypes = [P, vp]
     lib.attn_debug_dropout_mask.restype = ctypes.c_int
+    lib.attn_debug_mfma_rate.argtypes = [i32, i32, vp, vp, ctypes.POINTER(ctypes.c_double)]
+    lib.attn_debug_mfma_rate.restype = ctypes.c_int
     lib.attn_strerror.argtypes = [ctypes.c_int]
     lib.attn_strerror.restype = ctypes.c_char_p
     lib.attn_version.argtypes = []
@@ -261,3 +263,13 @@ def attn_debug_dropout_mask(B, H, N, dropout_p, seed, offset, device="cuda") -> 
     keep = torch.empty((B, H, N, N), dtype=torch.uint8, device=device)
     _check(load().attn_debug_dropout_mask(ctypes.byref(p), _ptr(keep)), "attn_debug_dropout_mask")
     return keep
+
+
+def attn_debug_mfma_rate(dtype: str, iters: int, sink: torch.Tensor) -> float:
+    """Launches the matrix-instruction-only kernel on the current stream; returns the FLOPs launched."""
+    fl = ctypes.c_double()
+    code = {"fp16": 0, "bf16": 1}[dtype]
+    stream = ctypes.c_void_p(int(torch.cuda.current_stream(sink.device).cuda_stream))
+    _check(load().attn_debug_mfma_rate(code, int(iters), _ptr(sink), stream, ctypes.byref(fl)),
+           "attn_debug_mfma_rate")
+    return float(fl.value)

@@ -212,6 +212,14 @@ int attn_debug_dropout_mask(const attn_params* p, uint8_t* keep) {
   return e == 0 ? ATTN_OK : ATTN_ERR_LAUNCH;
 }
 
+int attn_debug_mfma_rate(int32_t dtype, int32_t iters, float* sink, void* stream, double* flops) {
+  if (sink == nullptr) return ATTN_ERR_NULL;
+  if (dtype != ATTN_FP16 && dtype != ATTN_BF16) return ATTN_ERR_DTYPE;
+  if (iters < 1 || iters > (1 << 20)) return ATTN_ERR_SHAPE;
+  const int e = attn::launch_mfma_rate(dtype, iters, sink, (hipStream_t)stream, flops);
+  return e == 0 ? ATTN_OK : ATTN_ERR_LAUNCH;
+}
+
 const char* attn_strerror(int status) {
   switch (status) {
     case ATTN_OK: return "ok";

@@ -63,6 +63,8 @@ int launch_dropout_mask(const KArgs& a, uint8_t* keep, hipStream_t s);
 int launch_dkv_rs(const KArgs& a, int dtype, int d, bool causal, bool dropout, bool sparse, hipStream_t s);
 // dense forward with two wavefront groups in ping-pong (attn_fwd_pp.hip); sets its own work items
 int launch_fwd_pp(const KArgs& a, int dtype, int d, bool causal, bool dropout, hipStream_t s);
+// MFMA-only kernel for measuring the sustained matrix rate (attn_probe.hip); *flops = FLOPs launched
+int launch_mfma_rate(int dtype, int iters, float* sink, hipStream_t s, double* flops);
 
 #if defined(__HIPCC__)
 // ---------------------------------------------------------------- device helpers

@@ -94,3 +94,13 @@ def test_causal_paired_row_blocks_odd_count(N, d):
     res = hp.check_forward(t, dev, "bf16", 1 / math.sqrt(d), causal=True)
     print("causal pairs fwd", N, d, res)
     hp.assert_forward_ok(res)
+
+
+@pytest.mark.gpu
+def test_mfma_rate_probe_runs_and_reports_its_flops():
+    sink = torch.zeros(64, dtype=torch.float32, device="cuda")
+    for dtype in ("fp16", "bf16"):
+        flops = binding.attn_debug_mfma_rate(dtype, 100, sink)
+        assert flops == 2.0 * 32 * 32 * 16 * 4 * 100 * 4 * 2048
+    torch.cuda.synchronize()
+    assert float(sink.abs().sum()) == 0.0      # the sink is never written

@@ -101,6 +101,14 @@ def test_null_pointers_and_workspace(lib):
     assert lib.attn_blocksparse_bwd(ctypes.byref(p), *args_m, v, need) == -7     # dense size is too small
 
 
+def test_mfma_rate_probe_arguments(lib):
+    v, z = ctypes.c_void_p(0x1000), ctypes.c_void_p(0)
+    assert lib.attn_debug_mfma_rate(binding.ATTN_BF16, 10, z, z, None) == -1
+    assert lib.attn_debug_mfma_rate(7, 10, v, z, None) == -3
+    assert lib.attn_debug_mfma_rate(binding.ATTN_BF16, 0, v, z, None) == -2
+    assert lib.attn_debug_mfma_rate(binding.ATTN_FP16, (1 << 20) + 1, v, z, None) == -2
+
+
 def test_mask_arguments(lib):
     p = _params(N=256)
     v, z = ctypes.c_void_p(0x1000), ctypes.c_void_p(0)
