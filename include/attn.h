@@ -33,8 +33,11 @@
  *     Functions return ATTN_OK (0) or a negative attn_status; they never
  *     abort, throw, or print.
  *
- * Supported in this version: d in {32, 64, 128}; N a positive multiple of 128;
- * tau finite and > 0; 0 <= p_drop < 1; mask_block == 128.
+ * Supported in this version: d in {32, 64, 128}; any N >= 1 for the dense entry
+ * points (a last block of fewer than 128 tokens is handled inside the kernels:
+ * nothing outside the [B,H,N,d] tensors is read or written), N a multiple of
+ * 128 for the block-sparse ones; tau finite and > 0; 0 <= p_drop < 1;
+ * mask_block == 128.
  */
 #ifndef ATTN_H_
 #define ATTN_H_
@@ -49,7 +52,7 @@ extern "C" {
 typedef enum {
   ATTN_OK = 0,
   ATTN_ERR_NULL = -1,       /* a required pointer is NULL */
-  ATTN_ERR_SHAPE = -2,      /* B, H, N out of range, N not a multiple of 128, bad strides */
+  ATTN_ERR_SHAPE = -2,      /* B, H, N out of range, bad strides, block-sparse with N % 128 != 0 */
   ATTN_ERR_DTYPE = -3,      /* dtype is neither ATTN_FP16 nor ATTN_BF16 */
   ATTN_ERR_HEADDIM = -4,    /* d not in {32, 64, 128} */
   ATTN_ERR_DROPOUT_P = -5,  /* p_drop not in [0, 1) or NaN */

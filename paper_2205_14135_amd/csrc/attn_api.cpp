@@ -26,9 +26,10 @@ int check_params(const attn_params* p, Checked* out) {
   if (p->dtype != ATTN_FP16 && p->dtype != ATTN_BF16) return ATTN_ERR_DTYPE;
   if (p->d != 32 && p->d != 64 && p->d != 128) return ATTN_ERR_HEADDIM;
   if (p->B <= 0 || p->H <= 0 || p->N <= 0) return ATTN_ERR_SHAPE;
-  if (p->N % attn::kMaskBlock != 0) return ATTN_ERR_SHAPE;
+  if (p->N > (1 << 30)) return ATTN_ERR_SHAPE;
+  const int T = (p->N + attn::kMaskBlock - 1) / attn::kMaskBlock;   // a ragged last block is allowed (dense entry points)
   if ((int64_t)p->B * p->H > (int64_t)1 << 24) return ATTN_ERR_SHAPE;
-  if ((int64_t)p->B * p->H * (p->N / attn::kMaskBlock) > (int64_t)1 << 28) return ATTN_ERR_SHAPE;
+  if ((int64_t)p->B * p->H * T > (int64_t)1 << 28) return ATTN_ERR_SHAPE;
   int64_t sb = p->stride_b, sh = p->stride_h, sn = p->stride_n;
   if (sb == 0 && sh == 0 && sn == 0) {
     sn = p->d;
@@ -44,7 +45,7 @@ int check_params(const attn_params* p, Checked* out) {
   attn::KArgs& k = out->k;
   std::memset(&k, 0, sizeof(k));
   k.sb = sb; k.sh = sh; k.sn = sn;
-  k.B = p->B; k.H = p->H; k.N = p->N; k.T = p->N / attn::kMaskBlock;
+  k.B = p->B; k.H = p->H; k.N = p->N; k.T = T; k.Nr = T * attn::kMaskBlock;
   k.tau = p->softmax_scale;
   k.scale_log2 = (float)((double)p->softmax_scale * 1.4426950408889634);
   k.keep_scale = 1.0f / (1.0f - p->dropout_p);
@@ -65,6 +66,7 @@ int check_params(const attn_params* p, Checked* out) {
 int check_mask(const uint8_t* block_mask, int32_t mask_block, int64_t mask_stride_h, const attn_params* p) {
   if (block_mask == nullptr) return ATTN_ERR_NULL;
   if (mask_block != attn::kMaskBlock) return ATTN_ERR_MASK;
+  if (p->N % attn::kMaskBlock != 0) return ATTN_ERR_SHAPE;   // the block mask covers whole 128 x 128 blocks
   const int64_t T = p->N / attn::kMaskBlock;
   if (mask_stride_h < 0 || (mask_stride_h != 0 && mask_stride_h < T * T)) return ATTN_ERR_MASK;
   return ATTN_OK;
@@ -80,9 +82,11 @@ void set_items(attn::KArgs& k, int tiles_per_head) {
 struct WsLayout { size_t d_bytes, cnt_bytes, acc_bytes; };
 WsLayout ws_layout(const attn_params* p) {
   WsLayout w;
-  w.d_bytes = align_up(2 * (size_t)p->B * p->H * p->N * sizeof(float), 256);
+  const size_t T = ((size_t)p->N + attn::kMaskBlock - 1) / attn::kMaskBlock;
+  // two floats per row, rows padded to whole 128-blocks per head
+  w.d_bytes = align_up(2 * (size_t)p->B * p->H * T * attn::kMaskBlock * sizeof(float), 256);
   // column counts, then the segment list: one counter plus at most kMaxSegs entries per column
-  w.cnt_bytes = align_up(((size_t)p->B * p->H * (p->N / attn::kMaskBlock) * (1 + attn::kMaxSegs) + 64) * sizeof(int), 256);
+  w.cnt_bytes = align_up(((size_t)p->B * p->H * T * (1 + attn::kMaxSegs) + 64) * sizeof(int), 256);
   w.acc_bytes = align_up((size_t)p->B * p->H * p->N * p->d * sizeof(float), 256);
   return w;
 }
@@ -95,7 +99,7 @@ int fwd_common(const attn_params* p, const uint8_t* mask, int64_t mask_sh, bool 
   if (!Q || !K || !V || !O || !LSE) return ATTN_ERR_NULL;
   c.k.Q = Q; c.k.K = K; c.k.V = V; c.k.O = O; c.k.LSE = LSE;
   c.k.mask = mask; c.k.mask_sh = mask_sh;
-  set_items(c.k, c.k.N / 128);
+  set_items(c.k, c.k.T);
   const int e = attn::launch_fwd(c.k, c.dtype, c.d, c.causal, c.dropout, sparse, c.stream);
   return e == 0 ? ATTN_OK : ATTN_ERR_LAUNCH;
 }
@@ -113,7 +117,7 @@ int bwd_common(const attn_params* p, const uint8_t* mask, int64_t mask_sh, bool 
   c.k.Q = Q; c.k.K = K; c.k.V = V; c.k.O = const_cast<void*>(O); c.k.LSE = const_cast<float*>(LSE);
   c.k.dO = dO; c.k.dQ = dQ; c.k.dK = dK; c.k.dV = dV;
   c.k.Dvec = (float*)ws;
-  c.k.L2vec = c.k.Dvec + (size_t)p->B * p->H * p->N;
+  c.k.L2vec = c.k.Dvec + (size_t)p->B * p->H * c.k.Nr;
   if (sparse) {
     const WsLayout w = ws_layout(p);
     c.k.seglist = (int*)((char*)ws + w.d_bytes);
@@ -122,7 +126,7 @@ int bwd_common(const attn_params* p, const uint8_t* mask, int64_t mask_sh, bool 
     c.k.dVacc = (float*)((char*)ws + w.d_bytes + w.cnt_bytes + w.acc_bytes);
   }
   c.k.mask = mask; c.k.mask_sh = mask_sh;
-  set_items(c.k, c.k.N / 128);
+  set_items(c.k, c.k.T);
   hipEvent_t ev[4];
   if (events) {
     for (int i = 0; i < 4; ++i) {
@@ -152,7 +156,7 @@ size_t attn_bwd_workspace_bytes(const attn_params* p) {
 
 size_t attn_blocksparse_bwd_workspace_bytes(const attn_params* p) {
   Checked c;
-  if (check_params(p, &c) != ATTN_OK) return 0;
+  if (check_params(p, &c) != ATTN_OK || p->N % attn::kMaskBlock != 0) return 0;
   const WsLayout w = ws_layout(p);
   return w.d_bytes + w.cnt_bytes + 2 * w.acc_bytes;
 }
@@ -224,7 +228,7 @@ const char* attn_strerror(int status) {
   switch (status) {
     case ATTN_OK: return "ok";
     case ATTN_ERR_NULL: return "a required pointer is NULL";
-    case ATTN_ERR_SHAPE: return "unsupported shape or strides (N must be a positive multiple of 128)";
+    case ATTN_ERR_SHAPE: return "unsupported shape or strides (block-sparse: N must be a multiple of 128)";
     case ATTN_ERR_DTYPE: return "dtype must be ATTN_FP16 or ATTN_BF16";
     case ATTN_ERR_HEADDIM: return "head dimension must be 32, 64 or 128";
     case ATTN_ERR_DROPOUT_P: return "dropout_p must be in [0, 1)";

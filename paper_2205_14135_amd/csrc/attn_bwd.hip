@@ -33,14 +33,15 @@ template <typename T, int D>
 __global__ __launch_bounds__(256) void rowdot_kernel(const KArgs a) {
   typedef typename Vec<T>::x8 T8;
   constexpr int CPR = D / 8;  // lanes per row
-  const int64_t rows = (int64_t)a.B * a.H * a.N;
+  const int64_t rows = (int64_t)a.B * a.H * a.Nr;   // Nr = N rounded up to 128: the scratch vectors are padded per head
   const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (gid == 0 && a.seglist != nullptr) { a.seglist[0] = 0; a.seglist[1] = 0; }   // block-sparse: empty segment list, no blocks counted
   const int64_t row = gid / CPR;
   const int ch = (int)(gid % CPR);
+  const int64_t bh = row / a.Nr, i = row % a.Nr;
+  const bool real = row < rows && i < a.N;   // padding rows: D = 0, statistic = +inf (P = 0 there)
   float acc = 0.f;
-  if (row < rows) {
-    const int64_t bh = row / a.N, i = row % a.N;
+  if (real) {
     const int64_t off = (bh / a.H) * a.sb + (bh % a.H) * a.sh + i * a.sn + 8 * ch;
     const T8 g = *(const T8*)((const T*)a.dO + off);
     if (a.o_fp32) {
@@ -58,7 +59,7 @@ __global__ __launch_bounds__(256) void rowdot_kernel(const KArgs a) {
   for (int s = CPR / 2; s >= 1; s >>= 1) acc += __shfl_xor(acc, s);
   if (row < rows && ch == 0) {
     a.Dvec[row] = -acc;
-    const float lse = a.LSE[row];
+    const float lse = real ? a.LSE[bh * a.N + i] : -INFINITY;
     a.L2vec[row] = (lse == -INFINITY) ? INFINITY : lse * 1.4426950408889634f;
   }
 }
@@ -74,7 +75,7 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const KArgs a) {
 
   const int item = xcd_item(a.n_items, a.chunk);
   if (item < 0) return;
-  const int n_qt = a.N / 128;
+  const int n_qt = a.T;   // ceil(N / 128): the last block may be ragged
   // Work item = (head, row block).  Under the causal mask row block q sweeps 2 (q + 1) key tiles;
   // for dense d = 64 problems an item is the pair (n_qt - 1 - q, q), one per pass, so that every
   // workgroup does the same amount of work (at d = 128 the loop costs registers the kernel does
@@ -108,7 +109,9 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const KArgs a) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r = lane & 31, g = lane >> 5;
   const int q0 = qt * 128 + wave * 32;
-  const int qi = q0 + r;
+  // lanes beyond a ragged end work on a copy of the last row with P = 0 and store nothing
+  const bool row_ok = q0 + r < a.N;
+  const int qi = min(q0 + r, a.N - 1);
 
   T8 qf[KK], gf[KK];  // Q^T and dO^T fragments (B operands) of this lane's query
 #pragma unroll
@@ -119,8 +122,8 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const KArgs a) {
   }
   const float lse = a.LSE[(int64_t)bh * a.N + qi];
   // base-2 statistic; a row that saw no key has P = 0 everywhere
-  const float l2 = (lse == -INFINITY) ? INFINITY : lse * 1.4426950408889634f;
-  const float neg_d = a.Dvec[(int64_t)bh * a.N + qi];   // -D_i
+  const float l2 = (lse == -INFINITY || !row_ok) ? INFINITY : lse * 1.4426950408889634f;
+  const float neg_d = a.Dvec[(int64_t)bh * a.Nr + qi];   // -D_i
 
   f32x16 dq[DB];
 #pragma unroll
@@ -134,7 +137,7 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const KArgs a) {
   {
     int lim;
     if constexpr (SPARSE) lim = min(CAUSAL ? qt + 1 : a.T, (len + 127) / 128);
-    else lim = min(CAUSAL ? 2 * qt + 2 : a.N / TILE, (len + TILE - 1) / TILE);
+    else lim = CAUSAL ? min(2 * qt + 2, (len + TILE - 1) / TILE) : (len + TILE - 1) / TILE;   // len <= N
     if (qt * 128 >= len) lim = 0;
     it.init(SPARSE ? a.mask + (int64_t)h * a.mask_sh + (int64_t)qt * a.T : nullptr, 1, 0, lim);
   }
@@ -147,16 +150,16 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const KArgs a) {
   int jt = it.next();
   int buf = 0;
   if (jt >= 0) {
-    dma.copy(Kg + (int64_t)jt * TILE * a.sn, Ks[0]);
-    dma.copy(Vg + (int64_t)jt * TILE * a.sn, Vs[0]);
+    dma.copy_rows(Kg, a.sn, jt * TILE, a.N, Ks[0]);
+    dma.copy_rows(Vg, a.sn, jt * TILE, a.N, Vs[0]);
   }
   wait_async_copies();
   __syncthreads();   // tile 0 has landed, and so have the Q / dO fragments
   while (jt >= 0) {
     const int jn = it.next();
     if (jn >= 0) {   // next tile streams into the other buffer while this one is used
-      dma.copy(Kg + (int64_t)jn * TILE * a.sn, Ks[buf ^ 1]);
-      dma.copy(Vg + (int64_t)jn * TILE * a.sn, Vs[buf ^ 1]);
+      dma.copy_rows(Kg, a.sn, jn * TILE, a.N, Ks[buf ^ 1]);
+      dma.copy_rows(Vg, a.sn, jn * TILE, a.N, Vs[buf ^ 1]);
     }
     const T* Kt = Ks[buf];
     const T* Vt = Vs[buf];
@@ -253,7 +256,7 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const KArgs a) {
   }
   // the loop ends on a barrier (or never touched LDS): the tile buffers stage the output rows
   T* stage = (wave < 2 ? &Ks[0][0] + wave * 32 * D : &Vs[0][0] + (wave - 2) * 32 * D);
-  store_rows_coalesced<T, D>(stage, (T*)a.dQ + head_off + (int64_t)q0 * a.sn, a.sn, dq, a.tau);
+  store_rows_coalesced<T, D>(stage, (T*)a.dQ + head_off + (int64_t)q0 * a.sn, a.sn, dq, a.tau, a.N - q0);
   }  // for pass
 }
 
@@ -262,7 +265,7 @@ template <> constexpr int kDtype<__bf16> = 1;
 
 template <typename T, int D>
 int launch_bwd_td(const KArgs& a, bool causal, bool dropout, bool sparse, hipStream_t s, hipEvent_t* ev) {
-  const int64_t rows = (int64_t)a.B * a.H * a.N;
+  const int64_t rows = (int64_t)a.B * a.H * a.Nr;
   const int64_t threads = rows * (D / 8);
   if (ev) (void)hipEventRecord(ev[0], s);
   hipLaunchKernelGGL((rowdot_kernel<T, D>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, a);
@@ -273,7 +276,7 @@ int launch_bwd_td(const KArgs& a, bool causal, bool dropout, bool sparse, hipStr
   // dense causal d = 64 dQ items are pairs of row blocks
   KArgs aq = a;
   if (causal && !sparse && D == 64) {
-    aq.n_items = a.B * a.H * ((a.N / 128 + 1) / 2);
+    aq.n_items = a.B * a.H * ((a.T + 1) / 2);
     aq.chunk = (aq.n_items + kXcds - 1) / kXcds;
   }
   {

@@ -40,7 +40,7 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
   __shared__ __attribute__((aligned(16))) T8 Px[2][4][4][64];     // P exchange [buf][pair][chunk][lane]
   __shared__ uint32_t Kw[2][4][64];                                // dropout keep words [buf][pair][lane]
 
-  const int n_kt = a.N / 128;
+  const int n_kt = a.T;   // ceil(N / 128): the last key block may be ragged
   // Work assignment.  Dense: one key block per workgroup; under the causal mask key block k is
   // visited by N/64 - 2k query tiles, so a workgroup takes the pair (k, n_kt - 1 - k), one per
   // round, and all workgroups do the same amount of work.  Block-sparse: the first 8 * chunk
@@ -84,23 +84,26 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
   const int64_t head_off = (int64_t)b * a.sb + (int64_t)h * a.sh;
   const T* __restrict__ Qg = (const T*)a.Q + head_off;
   const T* __restrict__ Gg = (const T*)a.dO + head_off;
-  const float* __restrict__ Lg = a.L2vec + (int64_t)bh * a.N;   // base 2, +inf for fully masked rows
-  const float* __restrict__ Dg = a.Dvec + (int64_t)bh * a.N;
+  // padded to a multiple of 128 rows per head: +inf / 0 beyond a ragged end, so those query rows
+  // (whose Q and dO tile rows are copies of the last real row) contribute P = 0 and dS = 0
+  const float* __restrict__ Lg = a.L2vec + (int64_t)bh * a.Nr;   // base 2, +inf for fully masked rows
+  const float* __restrict__ Dg = a.Dvec + (int64_t)bh * a.Nr;
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const bool role_b = wave >= 4;
   const int pair = wave & 3;
   const int r = lane & 31, g = lane >> 5;
   const int kw0 = kt * 128 + pair * 32;
-  const int kj = kw0 + r;  // this lane's key
+  const int kj = kw0 + r;  // this lane's key (>= N beyond a ragged end: masked like a padded key, never stored)
 
   // loop-invariant B operands: K fragments for role A, V fragments for role B
   T8 kvf[KK];
   {
     const T* src = role_b ? (const T*)a.V : (const T*)a.K;
+    const int64_t row_off = head_off + (int64_t)min(kj, a.N - 1) * a.sn;
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk)
-      kvf[kk] = *(const T8*)(src + head_off + (int64_t)kj * a.sn + 16 * kk + 8 * g);
+      kvf[kk] = *(const T8*)(src + row_off + 16 * kk + 8 * g);
   }
   // The fragments must have arrived before the tile loop: a wait for them inside the loop would
   // also wait for the asynchronous tile copies in flight there.
@@ -120,7 +123,7 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
     it.init(a.mask + (int64_t)h * a.mask_sh + kt, a.T, CAUSAL ? kt : 0,
             kt * 128 >= len ? 0 : min(a.T, (len + 127) / 128), skip_blocks, take_blocks);
   else
-    it.init(nullptr, 0, CAUSAL ? 2 * kt : 0, kt * 128 >= len ? 0 : min(a.N / TILE, (len + TILE - 1) / TILE));
+    it.init(nullptr, 0, CAUSAL ? 2 * kt : 0, kt * 128 >= len ? 0 : (len + TILE - 1) / TILE);   // len <= N
   TrOffsets<D> tro;
   tro.init();
   TileAsync<T, D, 4> dma;   // the four role A wavefronts copy whole tiles
@@ -129,8 +132,8 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
   constexpr int kTileCopies = 2 * TileAsync<T, D, 4>::PER_WAVE;
   // starts the copies of tile t into ring slots (q4, g3)
   auto fetch_tile = [&](int t, int q4, int g3) {
-    dma.copy(Qg + (int64_t)t * TILE * a.sn, Qs[q4]);
-    dma.copy(Gg + (int64_t)t * TILE * a.sn, Gs[g3]);
+    dma.copy_rows(Qg, a.sn, t * TILE, a.N, Qs[q4]);
+    dma.copy_rows(Gg, a.sn, t * TILE, a.N, Gs[g3]);
     if (wave == 1) async_copy_b32(Lg + t * TILE + lane, __builtin_amdgcn_readfirstlane(lds_addr(Ls[g3])));
     if (wave == 2) async_copy_b32(Dg + t * TILE + lane, __builtin_amdgcn_readfirstlane(lds_addr(Ds[q4])));
   };
@@ -349,7 +352,7 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
     __syncthreads();   // role B has finished reading the tiles: they stage the output rows
     T* stage = (role_b ? &Gs[0][0] : &Qs[0][0]) + pair * 32 * D;
     store_rows_coalesced<T, D>(stage, (T*)(role_b ? a.dK : a.dV) + head_off + (int64_t)kw0 * a.sn, a.sn, acc,
-                               out_scale);
+                               out_scale, a.N - kw0);
   }
   if (!list_mode && last_round) return;
   __syncthreads();   // LDS is reused by the next segment / key block

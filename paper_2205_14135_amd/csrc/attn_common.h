@@ -22,8 +22,8 @@ struct KArgs {
   float* LSE;              // fwd: out; bwd: in        [B,H,N]
   const void* dO;          // bwd in
   void* dQ; void* dK; void* dV;   // bwd out
-  float* Dvec;             // bwd scratch: -D_i = -rowsum(dO_i o O_i)   [B,H,N]
-  float* L2vec;            // bwd scratch: L_i * log2(e), +inf where L_i = -inf   [B,H,N]
+  float* Dvec;             // bwd scratch: -D_i = -rowsum(dO_i o O_i)   [B,H,Nr], 0 for rows >= N
+  float* L2vec;            // bwd scratch: L_i * log2(e), +inf where L_i = -inf and for rows >= N   [B,H,Nr]
   int* colcnt;             // block-sparse bwd scratch: kept blocks per mask column   [B*H, T]
   int* seglist;            // block-sparse bwd scratch: [0] = number of entries, [1] = kept blocks in total,
                            // [2] = heavy threshold, from [kSegHeader]: entries (column * kMaxSegs + segment)
@@ -34,7 +34,8 @@ struct KArgs {
   int64_t mask_sh;
   const int* klen;         // key-padding lengths [B] or nullptr
   int64_t sb, sh, sn;      // element strides of the [B,H,N,d] tensors
-  int B, H, N, T;          // T = N / 128
+  int B, H, N, T;          // T = ceil(N / 128)
+  int Nr;                  // 128 T: rows per head of the backward scratch vectors
   float tau;               // softmax scale
   float scale_log2;        // tau * log2(e)
   float keep_scale;        // 1 / (1 - p_drop)

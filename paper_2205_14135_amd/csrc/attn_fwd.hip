@@ -39,7 +39,7 @@ __global__ __launch_bounds__(NT, 2) void fwd_kernel(const KArgs a) {
 
   const int item = xcd_item(a.n_items, a.chunk);
   if (item < 0) return;
-  const int n_qt = a.N / BR;
+  const int n_qt = a.T;   // ceil(N / BR): the last block may be ragged
   // Work item = (head, row block), heavy (late) blocks first under a causal mask.  For dense
   // causal d = 64 problems an item is the pair (n_qt - 1 - q, q), one block per pass, so that
   // every workgroup does the same amount of work.
@@ -62,7 +62,9 @@ __global__ __launch_bounds__(NT, 2) void fwd_kernel(const KArgs a) {
   const int lane = tid & 63, wave = tid >> 6;
   const int r = lane & 31, g = lane >> 5;
   const int q0 = qt * BR + wave * 32;  // first query row of this wavefront
-  const int qi = q0 + r;               // this lane's query row
+  // this lane's query row; lanes beyond a ragged end work on a copy of the last row and store nothing
+  const bool row_ok = q0 + r < a.N;
+  const int qi = min(q0 + r, a.N - 1);
 
   // Q^T fragments (B operand): lane holds query qi, d = 16 kk + 8 g .. +7
   T8 qf[KK];
@@ -84,7 +86,7 @@ __global__ __launch_bounds__(NT, 2) void fwd_kernel(const KArgs a) {
   {
     int lim;
     if constexpr (SPARSE) lim = min(CAUSAL ? qt + 1 : a.T, (len + 127) / 128);
-    else lim = min(CAUSAL ? 2 * qt + 2 : a.N / BC, (len + BC - 1) / BC);
+    else lim = CAUSAL ? min(2 * qt + 2, (len + BC - 1) / BC) : (len + BC - 1) / BC;   // len <= N
     if (qt * BR >= len) lim = 0;
     it.init(SPARSE ? a.mask + (int64_t)h * a.mask_sh + (int64_t)qt * a.T : nullptr, 1, 0, lim);
   }
@@ -98,16 +100,16 @@ __global__ __launch_bounds__(NT, 2) void fwd_kernel(const KArgs a) {
   int jt = it.next();
   int buf = 0;
   if (jt >= 0) {
-    dma.copy(Kg + (int64_t)jt * BC * a.sn, Ks[0]);
-    dma.copy(Vg + (int64_t)jt * BC * a.sn, Vs[0]);
+    dma.copy_rows(Kg, a.sn, jt * BC, a.N, Ks[0]);
+    dma.copy_rows(Vg, a.sn, jt * BC, a.N, Vs[0]);
   }
   wait_async_copies();
   __syncthreads();   // tile 0 has landed, and so have the Q fragments
   while (jt >= 0) {
     const int jn = it.next();
     if (jn >= 0) {   // the next tile streams into the other buffer while this one is used
-      dma.copy(Kg + (int64_t)jn * BC * a.sn, Ks[buf ^ 1]);
-      dma.copy(Vg + (int64_t)jn * BC * a.sn, Vs[buf ^ 1]);
+      dma.copy_rows(Kg, a.sn, jn * BC, a.N, Ks[buf ^ 1]);
+      dma.copy_rows(Vg, a.sn, jn * BC, a.N, Vs[buf ^ 1]);
     }
     const T* Kt = Ks[buf];
     const T* Vt = Vs[buf];
@@ -226,25 +228,27 @@ __global__ __launch_bounds__(NT, 2) void fwd_kernel(const KArgs a) {
   const float l_sum = l_run + xchg32(l_run);
   const float l_tot = qi < len ? l_sum : 0.f;   // padding rows: O = 0, LSE = -inf
   const float inv = l_tot > 0.f ? (DROPOUT ? a.keep_scale : 1.f) / l_tot : 0.f;
-  if (g == 0) {
+  if (g == 0 && row_ok) {
     const float lse = l_tot > 0.f ? (m_run + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f : -INFINITY;
     a.LSE[(int64_t)bh * a.N + qi] = lse;
   }
   if (a.o_fp32) {
     float* Og = (float*)a.O + head_off + (int64_t)qi * a.sn;
+    if (row_ok) {
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
+      for (int db = 0; db < DB; ++db)
 #pragma unroll
-      for (int i4 = 0; i4 < 4; ++i4) {
-        f32x4 v;
+        for (int i4 = 0; i4 < 4; ++i4) {
+          f32x4 v;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = o[db][4 * i4 + e] * inv;
-        *(f32x4*)(Og + 32 * db + 8 * i4 + 4 * g) = v;
-      }
+          for (int e = 0; e < 4; ++e) v[e] = o[db][4 * i4 + e] * inv;
+          *(f32x4*)(Og + 32 * db + 8 * i4 + 4 * g) = v;
+        }
+    }
   } else {
     // coalesced row stores through the (now idle) tile buffers: two wavefronts per buffer
     T* stage = (wave < 2 ? &Ks[0][0] + wave * 32 * D : &Vs[0][0] + (wave - 2) * 32 * D);
-    store_rows_coalesced<T, D>(stage, (T*)a.O + head_off + (int64_t)q0 * a.sn, a.sn, o, inv);
+    store_rows_coalesced<T, D>(stage, (T*)a.O + head_off + (int64_t)q0 * a.sn, a.sn, o, inv, a.N - q0);
   }
   }  // for pass
 }
@@ -253,7 +257,7 @@ template <typename T, int D>
 int launch_fwd_td(const KArgs& a_in, bool causal, bool dropout, bool sparse, hipStream_t s) {
   KArgs a = a_in;
   if (causal && !sparse && D == 64) {   // items are pairs of row blocks
-    a.n_items = a.B * a.H * ((a.N / BR + 1) / 2);
+    a.n_items = a.B * a.H * ((a.T + 1) / 2);
     a.chunk = (a.n_items + kXcds - 1) / kXcds;
   }
   const dim3 grid(kXcds * a.chunk), block(NT);
@@ -276,7 +280,7 @@ int launch_fwd_td(const KArgs& a_in, bool causal, bool dropout, bool sparse, hip
 
 // keep[bh][i][j] for the test hook: one thread per group of eight consecutive keys
 __global__ void dropout_mask_kernel(const KArgs a, uint8_t* keep) {
-  const int64_t ngrp = (int64_t)a.N / 8;
+  const int64_t ngrp = ((int64_t)a.N + 7) / 8;
   const int64_t total = (int64_t)a.B * a.H * a.N * ngrp;
   for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
        idx += (int64_t)gridDim.x * blockDim.x) {
@@ -290,8 +294,14 @@ __global__ void dropout_mask_kernel(const KArgs a, uint8_t* keep) {
       lo |= ((m >> f) & 1u) << (8 * f);
       hi |= ((m >> (4 + f)) & 1u) << (8 * f);
     }
-    *(uint32_t*)(keep + idx * 8) = lo;
-    *(uint32_t*)(keep + idx * 8 + 4) = hi;
+    if (a.N % 8 == 0) {
+      *(uint32_t*)(keep + idx * 8) = lo;
+      *(uint32_t*)(keep + idx * 8 + 4) = hi;
+    } else {   // rows of N bytes are not 4-byte aligned, and the last group of a row is partial
+      uint8_t* dst = keep + ((int64_t)bh * a.N + i) * a.N + 8 * (int64_t)g8;
+      const int n = min(8, a.N - 8 * (int)g8);
+      for (int f = 0; f < n; ++f) dst[f] = (uint8_t)((m >> f) & 1u);
+    }
   }
 }
 
@@ -321,7 +331,7 @@ int launch_fwd(const KArgs& a, int dtype, int d, bool causal, bool dropout, bool
 }
 
 int launch_dropout_mask(const KArgs& a, uint8_t* keep, hipStream_t s) {
-  const int64_t total = (int64_t)a.B * a.H * a.N * (a.N / 8);
+  const int64_t total = (int64_t)a.B * a.H * a.N * ((a.N + 7) / 8);
   const int blocks = (int)((total + 255) / 256 < 65536 ? (total + 255) / 256 : 65536);
   hipLaunchKernelGGL(dropout_mask_kernel, dim3(blocks), dim3(256), 0, s, a, keep);
   return (int)hipGetLastError();

@@ -45,8 +45,10 @@ __device__ __forceinline__ void fwd_pp_rows(const KArgs& a, const int bh, const 
   const bool group_b = wave >= 4;
   const int r = lane & 31, g = lane >> 5;
   const int q0 = qt * BRW + wave * 32;
-  const bool valid = q0 < a.N;          // N is a multiple of 128: whole wavefronts are in or out
-  const int qi = valid ? q0 + r : 0;
+  const bool valid = q0 < a.N;          // wavefronts past the end of the tensor only keep the barriers company
+  // lanes beyond a ragged end work on a copy of the last row and store nothing
+  const bool row_ok = q0 + r < a.N;
+  const int qi = min(q0 + r, a.N - 1);
 
   T8 qf[KK];
 #pragma unroll
@@ -62,10 +64,10 @@ __device__ __forceinline__ void fwd_pp_rows(const KArgs& a, const int bh, const 
 
   // key-padding mask: keys >= len are masked, rows >= len produce O = 0, LSE = -inf
   const int len = a.klen ? min(max(a.klen[b], 0), a.N) : a.N;
-  const int n_tiles = min(a.N / BC, (len + BC - 1) / BC);
+  const int n_tiles = (len + BC - 1) / BC;   // len <= N
   const int J = qt * BRW >= len ? 0 : (CAUSAL ? min(n_tiles, 4 * (qt + 1)) : n_tiles);
   if (J == 0) {   // nothing visible for any row of this workgroup: write zeros and leave
-    if (valid) {
+    if (row_ok) {
       if (g == 0) a.LSE[(int64_t)bh * a.N + qi] = -INFINITY;
       const int64_t o_off = head_off + (int64_t)qi * a.sn + (D / 2) * g;
       if (a.o_fp32) {
@@ -199,10 +201,10 @@ __device__ __forceinline__ void fwd_pp_rows(const KArgs& a, const int bh, const 
   };
 
   // ---- prologue: A copies K(0); B, which starts one block later, copies V(0) in slot 0
-  if (!group_b) dma.copy(Kg, Ks[0]);
+  if (!group_b) dma.copy_rows(Kg, a.sn, 0, a.N, Ks[0]);
   __syncthreads();
   if (group_b) {
-    dma.copy(Vg, Vs[0]);
+    dma.copy_rows(Vg, a.sn, 0, a.N, Vs[0]);
     __builtin_amdgcn_sched_barrier(0);
     __syncthreads();   // B runs one block behind A
   }
@@ -215,8 +217,8 @@ __device__ __forceinline__ void fwd_pp_rows(const KArgs& a, const int bh, const 
     __builtin_amdgcn_sched_barrier(0);
     // ---- X(j): start the copy of the next tile, then the online softmax
     if (j + 1 < J) {
-      if (!group_b) dma.copy(Kg + (int64_t)(j + 1) * BC * a.sn, Ks[(j + 1) & 1]);
-      else dma.copy(Vg + (int64_t)(j + 1) * BC * a.sn, Vs[(j + 1) & 1]);
+      if (!group_b) dma.copy_rows(Kg, a.sn, (j + 1) * BC, a.N, Ks[(j + 1) & 1]);
+      else dma.copy_rows(Vg, a.sn, (j + 1) * BC, a.N, Vs[(j + 1) & 1]);
     }
     if (active(j)) do_softmax(j);
     __builtin_amdgcn_sched_barrier(0);
@@ -232,24 +234,26 @@ __device__ __forceinline__ void fwd_pp_rows(const KArgs& a, const int bh, const 
   const float l_sum = l_run + xchg32(l_run);
   const float l_tot = qi < len ? l_sum : 0.f;   // padding rows: O = 0, LSE = -inf
   const float inv = l_tot > 0.f ? (DROPOUT ? a.keep_scale : 1.f) / l_tot : 0.f;
-  if (g == 0) {
+  if (g == 0 && row_ok) {
     const float lse = l_tot > 0.f ? (m_run + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f : -INFINITY;
     a.LSE[(int64_t)bh * a.N + qi] = lse;
   }
   if (a.o_fp32) {
     float* Og = (float*)a.O + head_off + (int64_t)qi * a.sn;
+    if (row_ok) {
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
+      for (int db = 0; db < DB; ++db)
 #pragma unroll
-      for (int i4 = 0; i4 < 4; ++i4) {
-        f32x4 v;
+        for (int i4 = 0; i4 < 4; ++i4) {
+          f32x4 v;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = o[db][4 * i4 + e] * inv;
-        *(f32x4*)(Og + 32 * db + 8 * i4 + 4 * g) = v;
-      }
+          for (int e = 0; e < 4; ++e) v[e] = o[db][4 * i4 + e] * inv;
+          *(f32x4*)(Og + 32 * db + 8 * i4 + 4 * g) = v;
+        }
+    }
   } else {
     T* stage = wave < 4 ? &Ks[0][0] + wave * 32 * D : &Vs[0][0] + (wave - 4) * 32 * D;
-    store_rows_coalesced<T, D>(stage, (T*)a.O + head_off + (int64_t)q0 * a.sn, a.sn, o, inv);
+    store_rows_coalesced<T, D>(stage, (T*)a.O + head_off + (int64_t)q0 * a.sn, a.sn, o, inv, a.N - q0);
   }
 }
 

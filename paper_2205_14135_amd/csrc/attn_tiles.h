@@ -5,6 +5,17 @@
 
 namespace attn {
 
+// Lane index read by an instruction the compiler will not move: address arithmetic of a rarely
+// taken path that starts from it stays inside that path instead of being hoisted out of the tile
+// loop, where it would occupy registers for the whole kernel.
+__device__ __forceinline__ int lane_id_here() {
+  int lane = 0;
+#if defined(__HIP_DEVICE_COMPILE__)
+  asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(lane));
+#endif
+  return lane;
+}
+
 // Asynchronous copy of a [64][D] tile from global memory straight into swizzled LDS (no register
 // staging, no LDS store instructions): each global_load_lds_dwordx4 moves 64 lanes x 16 bytes to
 // 1 KB of consecutive LDS, so lane l of copy q lands on row q*(64/CPR) + l/CPR, physical chunk
@@ -33,6 +44,26 @@ template <typename T, int D, int NW> struct TileDma {
 #else
     (void)g_row0; (void)lds_tile;
 #endif
+  }
+  // The last tile of a tensor whose row count is not a multiple of 64: only rows_valid (>= 1) rows
+  // exist; the LDS rows beyond them receive a copy of the last valid row (finite values that the
+  // kernels mask), so that nothing outside the tensor is read.
+  __device__ __forceinline__ void copy_tail(const T* g_row0, T* lds_tile, int64_t sn, int rows_valid) const {
+#if defined(__HIP_DEVICE_COMPILE__)
+    const int lane_row = lane_id_here() / CPR;
+#pragma unroll
+    for (int p = 0; p < PER_WAVE; ++p) {
+      const int excess = max((wave * PER_WAVE + p) * RPC + lane_row - (rows_valid - 1), 0);   // rows past the last one
+      __builtin_amdgcn_global_load_lds(g_row0 + (goff[p] - excess * sn), lds_tile + (wave * PER_WAVE + p) * 512, 16, 0, 0);
+    }
+#else
+    (void)g_row0; (void)lds_tile; (void)sn; (void)rows_valid;
+#endif
+  }
+  // tile whose first row is row0 of a tensor with n_rows rows (row0 < n_rows)
+  __device__ __forceinline__ void copy_rows(const T* g, int64_t sn, int row0, int n_rows, T* lds_tile) const {
+    if (row0 + 64 <= n_rows) copy(g + (int64_t)row0 * sn, lds_tile);
+    else copy_tail(g + (int64_t)row0 * sn, lds_tile, sn, n_rows - row0);
   }
 };
 
@@ -116,6 +147,24 @@ template <typename T, int D, int NW> struct TileAsync {
 #pragma unroll
     for (int p = 0; p < PER_WAVE; ++p) async_copy_b128(g_row0, goff[p], base + p * 1024);
   }
+  // The last tile of a tensor whose row count is not a multiple of 64: only rows_valid (>= 1) rows
+  // exist; the LDS rows beyond them receive a copy of the last valid row (finite values that the
+  // kernels mask), so that nothing outside the tensor is read.
+  __device__ __forceinline__ void copy_tail(const T* g_row0, const T* lds_tile, int64_t sn, int rows_valid) const {
+    const int lane_row = lane_id_here() / CPR;
+    const uint32_t row_bytes = (uint32_t)sn * (uint32_t)sizeof(T);   // 64 rows span less than 2^31 bytes
+    const uint32_t base = __builtin_amdgcn_readfirstlane(lds_addr(lds_tile) + (wave * PER_WAVE) * 1024);
+#pragma unroll
+    for (int p = 0; p < PER_WAVE; ++p) {
+      const int excess = max((wave * PER_WAVE + p) * RPC + lane_row - (rows_valid - 1), 0);   // rows past the last one
+      async_copy_b128(g_row0, goff[p] - (uint32_t)excess * row_bytes, base + p * 1024);
+    }
+  }
+  // tile whose first row is row0 of a tensor with n_rows rows (row0 < n_rows)
+  __device__ __forceinline__ void copy_rows(const T* g, int64_t sn, int row0, int n_rows, const T* lds_tile) const {
+    if (row0 + 64 <= n_rows) copy(g + (int64_t)row0 * sn, lds_tile);
+    else copy_tail(g + (int64_t)row0 * sn, lds_tile, sn, n_rows - row0);
+  }
 };
 
 // Per-lane LDS offsets for the transposing read of a swizzled tile (see attn_fwd.hip for the
@@ -165,10 +214,12 @@ __device__ __forceinline__ void store_rows(T* dst_row, const f32x16 (&acc)[D / 3
 // LDS area of 32 * D elements so that global memory sees whole 16-byte-per-lane row segments
 // (a token row is written by D/8 consecutive lanes) instead of 8-byte pieces 2*D bytes apart.
 // The area is unpadded; the 16-byte chunk index is XORed with the row to spread the banks.
-// dst_row0 points at the row of the wavefront's first token.
+// dst_row0 points at the row of the wavefront's first token; only the first rows_valid of the 32
+// rows exist in the destination (fewer than 32 on the last block of a ragged tensor; may be <= 0).
 template <typename T, int D>
 __device__ __forceinline__ void store_rows_coalesced(T* stage, T* dst_row0, int64_t sn,
-                                                     const f32x16 (&acc)[D / 32], float scale) {
+                                                     const f32x16 (&acc)[D / 32], float scale,
+                                                     int rows_valid = 32) {
   typedef typename Vec<T>::x4 T4;
   typedef typename Vec<T>::x8 T8;
   constexpr int CPR = D / 8;         // 16-byte chunks per row
@@ -189,7 +240,7 @@ __device__ __forceinline__ void store_rows_coalesced(T* stage, T* dst_row0, int6
   for (int p = 0; p < 32 / RPP; ++p) {
     const int row = p * RPP + lane / CPR, ch = lane % CPR;
     const T8 v = *(const T8*)(stage + row * D + 8 * (ch ^ (row & (CPR - 1))));
-    *(T8*)(dst_row0 + (int64_t)row * sn + 8 * ch) = v;
+    if (row < rows_valid) *(T8*)(dst_row0 + (int64_t)row * sn + 8 * ch) = v;
   }
 }
 

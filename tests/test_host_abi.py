@@ -63,8 +63,8 @@ def test_struct_layout_matches_c():
     (dict(dtype=2), -3),
     (dict(d=96), -4),
     (dict(d=16), -4),
-    (dict(N=100), -2),
     (dict(N=0), -2),
+    (dict(N=-128), -2),
     (dict(B=0), -2),
     (dict(stride_b=8192, stride_h=8192, stride_n=60), -2),
     (dict(stride_b=8192, stride_h=8192, stride_n=68), -2),
@@ -117,6 +117,14 @@ def test_mask_arguments(lib):
     assert lib.attn_blocksparse_fwd(ctypes.byref(p), v, 128, 3, v, v, v, v, v) == -8
     assert lib.attn_blocksparse_fwd(ctypes.byref(p), v, 128, -4, v, v, v, v, v) == -8
     assert lib.attn_debug_dropout_mask(ctypes.byref(p), z) == -1
+    # a ragged last block is fine for the dense entry points but not under a 128 x 128 block mask
+    ragged = _params(N=200)
+    assert lib.attn_blocksparse_fwd(ctypes.byref(ragged), v, 128, 0, v, v, v, v, v) == -2
+    assert lib.attn_blocksparse_bwd(ctypes.byref(ragged), v, 128, 0, *([v] * 9), v, 1 << 20) == -2
+    assert lib.attn_blocksparse_bwd_workspace_bytes(ctypes.byref(ragged)) == 0
+    # dense backward scratch: two floats per row, rows padded to whole blocks of 128 per head
+    assert lib.attn_bwd_workspace_bytes(ctypes.byref(ragged)) == 2 * 256 * 4
+    assert lib.attn_bwd_workspace_bytes(ctypes.byref(_params(N=1))) == 2 * 128 * 4
 
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
