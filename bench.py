@@ -287,6 +287,34 @@ def memory_and_naive(steps):
         del g
 
 
+def naive_steps(cfg, steps):
+    """Algorithm 0 of the paper with PyTorch ops (S and P written to and read from HBM), forward and
+    autograd backward, at the shape of a dense workload: run under rocprofv3 to count its HBM bytes."""
+    import torch
+    dev = torch.device("cuda:0")
+    dt = torch.bfloat16 if cfg["dtype"] == "bf16" else torch.float16
+    shape = (cfg["B"], cfg["H"], cfg["N"], cfg["d"])
+    torch.manual_seed(0)
+    g = {k: torch.randn(shape, device=dev, dtype=dt, requires_grad=(k != "dO")) for k in ("Q", "K", "V", "dO")}
+    tau = 1.0 / math.sqrt(cfg["d"])
+    causal = None
+    if cfg["causal"]:
+        causal = torch.ones(cfg["N"], cfg["N"], dtype=torch.bool, device=dev).triu(1)
+    for _ in range(steps):
+        S = torch.matmul(g["Q"], g["K"].transpose(-1, -2)) * tau
+        if causal is not None:
+            S = S.masked_fill(causal, float("-inf"))
+        P = torch.softmax(S, dim=-1)
+        if cfg["p"] > 0:
+            P = torch.nn.functional.dropout(P, cfg["p"])
+        O = torch.matmul(P, g["V"])
+        O.backward(g["dO"])
+        for k in ("Q", "K", "V"):
+            g[k].grad = None
+    torch.cuda.synchronize()
+    print(json.dumps({"naive_steps": steps, "shape": list(shape), "dtype": cfg["dtype"]}))
+
+
 def cpu_baseline(cfg, run, budget_s=12.0, max_s=30.0):
     """Times the fp64 oracle (forward + backward of whole heads) on the host cores."""
     import numpy as np
@@ -359,6 +387,9 @@ def main():
                     help="only: block-sparse runtime against mask density at N=4096 (JSON lines on stderr)")
     ap.add_argument("--memory-table", action="store_true",
                     help="only: memory and time against a materialise-S attention in PyTorch ops (JSON lines on stderr)")
+    ap.add_argument("--naive-steps", type=int, default=0,
+                    help="only: run this many forward+backward steps of a materialise-S attention in PyTorch ops at the "
+                         "workload's shape (comparison system for the HBM byte counters)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a 1 GiB elementwise copy kernel (reference for the HBM byte counters)")
     args = ap.parse_args()
@@ -381,6 +412,10 @@ def main():
             torch.mul(src, 1.0, out=dst)     # an ordinary elementwise kernel: reads 1 GiB, writes 1 GiB
         torch.cuda.synchronize()
         print(json.dumps({"copy_bytes_read": src.numel() * 4, "copy_bytes_written": src.numel() * 4, "launches": 3}))
+        return
+    if args.naive_steps > 0:
+        cfg = wl[args.workload]
+        naive_steps(cfg, args.naive_steps)
         return
     from paper_2205_14135_amd import binding, inputs
     binding.load()
