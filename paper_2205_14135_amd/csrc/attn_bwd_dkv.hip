@@ -10,7 +10,8 @@
 // so each wavefront needs half of the accumulators and operand fragments (<= 256 registers, two
 // wavefronts per SIMD), the four tile products are done once each, and the two different
 // instruction streams on a SIMD overlap MFMA with the exp / dS VALU work.  B needs A's P: A
-// leaves it (16-bit, in B's own register layout, plus the dropout keep bits) in LDS, and B runs
+// leaves it (as fp16 whatever the tensor type, in B's own register layout, plus the dropout keep
+// bits) in LDS, and B runs
 // its dS / dK part one tile behind, so one workgroup barrier per tile orders everything.
 // Tiles arrive by asynchronous global-to-LDS copies (no staging registers, no LDS store
 // instructions).  Issuing a tile's 34 copies stalls a wavefront for hundreds of clocks (the
@@ -37,7 +38,10 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
   __shared__ __attribute__((aligned(16))) T Gs[3][TILE * D];      // dO tiles
   __shared__ __attribute__((aligned(16))) float Ls[3][TILE];      // base-2 row statistic
   __shared__ __attribute__((aligned(16))) float Ds[4][TILE];      // -D_i
-  __shared__ __attribute__((aligned(16))) T8 Px[2][4][4][64];     // P exchange [buf][pair][chunk][lane]
+  // P exchange [buf][pair][chunk][lane]: always fp16 (11 significant bits, more than bf16 keeps; P <= 1
+  // and anything below 2^-24 contributes nothing to dS), because role B can multiply an fp16 half
+  // by an fp32 value in one mixed-precision instruction, with no unpacking
+  __shared__ __attribute__((aligned(16))) f16x8 Px[2][4][4][64];
   __shared__ uint32_t Kw[2][4][64];                                // dropout keep words [buf][pair][lane]
 
   const int n_kt = a.T;   // ceil(N / 128): the last key block may be ragged
@@ -249,6 +253,7 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
           if (kj >= len) sd[qb][i] = -INFINITY;
     }
     T8 pf[4], pfull[4];
+    f16x8 ph[4];
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
@@ -261,6 +266,7 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
           if (CAUSAL && kj > i0 + 32 * qb + 8 * i4 + 4 * g + e) p = 0.f;
           const int cc = 2 * qb + (i4 >> 1), t = 4 * (i4 & 1) + e;
           pfull[cc][t] = (T)p;
+          ph[cc][t] = (_Float16)p;
           if constexpr (DROPOUT) {
             const bool keep = (kw[qb][e] >> (8 * i4)) & 1u;
             pf[cc][t] = (T)(keep ? p : 0.f);
@@ -268,7 +274,7 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
         }
       }
 #pragma unroll
-    for (int cc = 0; cc < 4; ++cc) Px[p2][pair][cc][lane] = pfull[cc];
+    for (int cc = 0; cc < 4; ++cc) Px[p2][pair][cc][lane] = ph[cc];
     if constexpr (DROPOUT) col_product(Gs[g3], pf);        // dV^T += dO^T P_dropped
     else col_product(Gs[g3], pfull);
   };
@@ -276,7 +282,8 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
   auto role_b_ds_dk = [&](int q4, int p2) {
     uint32_t kw[2][4] = {{0, 0, 0, 0}, {0, 0, 0, 0}};
     if constexpr (DROPOUT) keep_words(Kw[p2][pair][lane], kw);
-    T8 pin[4], dsf[4];
+    f16x8 pin[4];
+    T8 dsf[4];
 #pragma unroll
     for (int cc = 0; cc < 4; ++cc) pin[cc] = Px[p2][pair][cc][lane];
 #pragma unroll
@@ -294,7 +301,8 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
             const bool keep = (kw[qb][e] >> (8 * i4)) & 1u;
             dpv = (keep ? dpv * a.keep_scale : 0.f) + d4[e];
           }
-          dsf[cc][t] = (T)((float)pin[cc][t] * dpv);
+          // (an fma with an fp16 operand is one v_fma_mix_f32: the half is widened inside the instruction)
+          dsf[cc][t] = (T)__builtin_fmaf((float)pin[cc][t], dpv, 0.f);
         }
       }
     col_product(Qs[q4], dsf);                               // dK^T += Q^T dS
