@@ -80,6 +80,37 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
+// acc + the sum of the eight 16-bit values of v, each widened exactly (four two-element dot products
+// with ones: half an instruction per element)
+__device__ __forceinline__ float sum8(bf16x8 v, float acc) {
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  const bf16x2 one = {(__bf16)1.f, (__bf16)1.f};
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const bf16x2 pr = {v[2 * k], v[2 * k + 1]};
+    acc = __builtin_amdgcn_fdot2_f32_bf16(pr, one, acc, false);
+  }
+  return acc;
+}
+__device__ __forceinline__ float sum8(f16x8 v, float acc) {
+  typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+  const f16x2 one = {(_Float16)1.f, (_Float16)1.f};
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const f16x2 pr = {v[2 * k], v[2 * k + 1]};
+    acc = __builtin_amdgcn_fdot2(pr, one, acc, false);
+  }
+  return acc;
+}
+
+// Online softmax, when the reference of a row is moved: only when the maximum of a new tile
+// exceeds the reference by more than this (base-2 exponent units; the first tile always does).
+// Probabilities then reach 2^kLazyRescale at most, exactly representable scalings in both 16-bit
+// types.  What makes a lagging reference as accurate as the exact running maximum is that O is
+// normalised by the sum of the ROUNDED 16-bit probabilities, the very weights the second product
+// used: O stays a convex combination of V rows whatever the reference is.
+constexpr float kLazyRescale = 8.0f;
+
 // Philox-4x32-10 (Salmon et al., SC'11): counter (c0..c3), key (k0,k1) -> 4 words.
 __device__ __forceinline__ u32x4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
                                                uint32_t k0, uint32_t k1) {

@@ -8,6 +8,15 @@
 // never travel to HBM between tiles (the paper's K/V-outer order re-reads and re-writes them
 // on every pass).  K/V tiles of 64 keys are staged in LDS.
 //
+// Online softmax, two departures from the printed recurrence that leave the result the same up
+// to rounding.  (1) The reference m of a row is moved (and O, l rescaled) only when a tile's
+// maximum exceeds it by more than 2^kLazyRescale: any reference gives the same softmax in exact
+// arithmetic, and most tiles then skip the rescaling of the whole O accumulator.  (2) O is divided
+// by the sum of the probabilities AS ROUNDED to 16 bits for the second product, not by l: O is
+// then a convex combination of V rows with exactly the weights that were used, which is what
+// keeps a lagging reference accurate (with the exact l a peaked row would see the rounding of its
+// one large weight in full).  The saved statistic L = m + ln l uses the exact fp32 l.
+//
 // Register layout trick: the kernel computes S^T = K Q^T with 32x32x16 MFMA, so that a lane
 // holds 16 keys of ONE query (accumulator register i of key block kb is key
 // 32 kb + 8 (i/4) + 4 (lane/32) + i%4, query lane%32).  Row max / row sum are then in-lane
@@ -77,8 +86,10 @@ __global__ __launch_bounds__(NT, 2) void fwd_kernel(const KArgs a) {
   for (int db = 0; db < DB; ++db)
 #pragma unroll
     for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
-  float m_run = -INFINITY;  // running max of the scaled logits, base-2 domain
-  float l_run = 0.f;        // this lane's share of the running row sum
+  float m_run = -INFINITY;  // reference of the row's probabilities, base-2 domain: lags the running
+                            // maximum of the scaled logits by at most kLazyRescale
+  float l_run = 0.f;        // this lane's share of the exact running row sum (for the saved statistic)
+  float lr_run = 0.f;       // its share of the sum of the rounded probabilities (normalises O)
 
   // key-padding mask: keys >= len are masked, rows >= len produce O = 0, LSE = -inf
   const int len = a.klen ? min(max(a.klen[b], 0), a.N) : a.N;
@@ -159,13 +170,15 @@ __global__ __launch_bounds__(NT, 2) void fwd_kernel(const KArgs a) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[kb][i]);
       mx = fmaxf(mx, xchg32(mx));
-      // rescale only when some row of this wavefront saw a new maximum (wavefront-uniform branch)
-      if (__builtin_amdgcn_ballot_w64(mx * c > m_run) != 0) {
+      // move the reference (and rescale O) only when some row of this wavefront outgrew it by more
+      // than kLazyRescale (wavefront-uniform branch): on most tiles nothing is rescaled
+      if (__builtin_amdgcn_ballot_w64(mx * c > m_run + kLazyRescale) != 0) {
         const float m_new = fmaxf(m_run, mx * c);
         const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
         const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
         m_run = m_new;
         l_run *= alpha;
+        lr_run *= alpha;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -182,8 +195,17 @@ __global__ __launch_bounds__(NT, 2) void fwd_kernel(const KArgs a) {
           psum += p;
         }
       l_run += psum;
-      // ---- dropout on the unnormalised probabilities (the row sum above is undropped)
+      // ---- dropout on the unnormalised probabilities (both row sums are undropped)
       if constexpr (DROPOUT) {
+        float part[4];
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc) {
+          T8 all;
+#pragma unroll
+          for (int t = 0; t < 8; ++t) all[t] = (T)s[cc >> 1][8 * (cc & 1) + t];
+          part[cc] = sum8(all, 0.f);
+        }
+        lr_run += (part[0] + part[1]) + (part[2] + part[3]);
         const KeepLQ kq = keep_tile_lane_query(k0, qi, bh, g, a.offset_lo, a.seed_lo, a.seed_hi, a.drop_thr);
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
@@ -199,6 +221,12 @@ __global__ __launch_bounds__(NT, 2) void fwd_kernel(const KArgs a) {
       for (int cc = 0; cc < 4; ++cc)
 #pragma unroll
         for (int t = 0; t < 8; ++t) pf[cc][t] = (T)s[cc >> 1][8 * (cc & 1) + t];
+      if constexpr (!DROPOUT) {   // O is normalised by the sum of exactly these rounded weights
+        float part[4];
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc) part[cc] = sum8(pf[cc], 0.f);
+        lr_run += (part[0] + part[1]) + (part[2] + part[3]);
+      }
       // ---- O^T += V^T P^T
       {
         auto v_frag = [&](int f) {   // f = DB cc + db: consecutive MFMAs hit different accumulators
@@ -226,8 +254,9 @@ __global__ __launch_bounds__(NT, 2) void fwd_kernel(const KArgs a) {
 
   // ---- epilogue: normalise, apply the dropout scale, write O and L once
   const float l_sum = l_run + xchg32(l_run);
+  const float lr_sum = lr_run + xchg32(lr_run);
   const float l_tot = qi < len ? l_sum : 0.f;   // padding rows: O = 0, LSE = -inf
-  const float inv = l_tot > 0.f ? (DROPOUT ? a.keep_scale : 1.f) / l_tot : 0.f;
+  const float inv = (l_tot > 0.f && lr_sum > 0.f) ? (DROPOUT ? a.keep_scale : 1.f) / lr_sum : 0.f;
   if (g == 0 && row_ok) {
     const float lse = l_tot > 0.f ? (m_run + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f : -INFINITY;
     a.LSE[(int64_t)bh * a.N + qi] = lse;

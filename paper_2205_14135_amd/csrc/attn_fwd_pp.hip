@@ -9,14 +9,18 @@
 // workgroup's 256 query rows, and workgroup barriers keep group B exactly one block behind
 // group A: while one group issues MFMA the other issues the softmax VALU work.
 //
-// K and V tiles are double buffered in LDS (unpadded, XOR-swizzled) and shared by both groups.
+// K and V tiles sit in rings of three LDS buffers (unpadded, XOR-swizzled) shared by both groups.
 // In global slot numbers (slot 2j: A in M(j), B in X(j-1); slot 2j+1: A in X(j), B in M(j)) K(t)
-// is read in slots 2t, 2t+1 and V(t) in slots 2t+2, 2t+3, so K(t) may be written in slots 2t-2,
-// 2t-1 and V(t) in slots 2t, 2t+1.  Tiles arrive by asynchronous global-to-LDS copies issued from
-// the vector blocks, which use no LDS themselves: group A copies K(j+1) at the start of its X(j)
-// (slot 2j+1) and group B copies V(j+1) at the start of its X(j) (slot 2j+2); the barrier that
-// closes the block waits for the copies, so they are visible from the next slot on.  The matrix
-// blocks carry no staging work at all.
+// is read in slots 2t, 2t+1 and V(t) in slots 2t+2, 2t+3.  Tiles arrive by asynchronous
+// global-to-LDS copies that the compiler does not track; group A copies the K tiles and group B
+// the V tiles.  Issuing a tile's copy instructions blocks a wavefront for hundreds of clocks (the
+// vector memory path takes 64 bytes per clock), so a wavefront issues tile j + 1 at the END of its
+// matrix block M(j), the shorter of the two blocks, where it would otherwise wait at the barrier
+// for the other group's vector block, and waits for the copy only at the end of its own X(j): the
+// copy has a whole block to land and its latency never shows.  (Measured against issuing at the
+// start or at the end of the vector block, or half and half: this placement is the fastest.)  The
+// third V buffer is what allows it: when a group B wavefront leaves M(j), its neighbours may still
+// be reading V(j-1).
 #include "attn_common.h"
 #include "attn_tiles.h"
 
@@ -29,8 +33,8 @@ constexpr int NT = 512;
 
 // One block of 256 query rows (row block qt of head bh) against all the keys it sees.
 template <typename T, int D, bool CAUSAL, bool DROPOUT>
-__device__ __forceinline__ void fwd_pp_rows(const KArgs& a, const int bh, const int qt, T (&Ks)[2][BC * D],
-                                            T (&Vs)[2][BC * D]) {
+__device__ __forceinline__ void fwd_pp_rows(const KArgs& a, const int bh, const int qt, T (&Ks)[3][BC * D],
+                                            T (&Vs)[3][BC * D]) {
   typedef typename Vec<T>::x8 T8;
   typedef typename Vec<T>::x4 T4;
   constexpr int KK = D / 16, DB = D / 32;
@@ -60,7 +64,10 @@ __device__ __forceinline__ void fwd_pp_rows(const KArgs& a, const int bh, const 
   for (int db = 0; db < DB; ++db)
 #pragma unroll
     for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
-  float m_run = -INFINITY, l_run = 0.f;
+  // m_run: reference of the row's probabilities (base 2; lags the running maximum by at most
+  // kLazyRescale); l_run: this lane's share of the exact row sum (for the saved statistic);
+  // lr_run: its share of the sum of the rounded probabilities (normalises O)
+  float m_run = -INFINITY, l_run = 0.f, lr_run = 0.f;
 
   // key-padding mask: keys >= len are masked, rows >= len produce O = 0, LSE = -inf
   const int len = a.klen ? min(max(a.klen[b], 0), a.N) : a.N;
@@ -79,8 +86,10 @@ __device__ __forceinline__ void fwd_pp_rows(const KArgs& a, const int bh, const 
     return;
   }
 
-  TileDma<T, D, 4> dma;   // the four wavefronts of a group copy a whole tile
+  typedef TileAsync<T, D, 4> Dma;   // the four wavefronts of a group copy a whole tile
+  Dma dma;
   dma.init(a.sn, wave & 3);
+  const T* __restrict__ Tg = group_b ? Vg : Kg;   // the tensor this group copies
   TrOffsets<D> tro;
   tro.init();
   const float c = a.scale_log2;
@@ -103,9 +112,7 @@ __device__ __forceinline__ void fwd_pp_rows(const KArgs& a, const int bh, const 
 
   // M block: O^T += V(jv)^T P^T (if do_pv) followed by S^T = K(js) Q^T (if do_s), as one
   // software-pipelined stream of 4*DB + 2*KK MFMAs.
-  auto do_M = [&](bool do_pv, int jv, bool do_s, int js) {
-    const T* vbuf = Vs[jv & 1];
-    const T* kbuf = Ks[js & 1];
+  auto do_M = [&](bool do_pv, const T* vbuf, bool do_s, const T* kbuf) {
     constexpr int NV = 4 * DB, NK = 2 * KK;
     T8 ring[PF];
     if (do_pv) {
@@ -159,15 +166,15 @@ __device__ __forceinline__ void fwd_pp_rows(const KArgs& a, const int bh, const 
 #pragma unroll
       for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[kb][i]);
     mx = fmaxf(mx, xchg32(mx)) * c;
-    // rescale only when some row of this wavefront saw a new maximum (wavefront-uniform branch).
-    // The reference must be the true running maximum: then the largest probability of a row is
-    // exactly 1 in 16 bits, which is what keeps peaked rows within the forward tolerance.
-    if (__builtin_amdgcn_ballot_w64(mx > m_run) != 0) {
+    // move the reference (and rescale O) only when some row of this wavefront outgrew it by more
+    // than kLazyRescale (wavefront-uniform branch): on most tiles nothing is rescaled
+    if (__builtin_amdgcn_ballot_w64(mx > m_run + kLazyRescale) != 0) {
       const float m_new = fmaxf(m_run, mx);
       const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
       const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
       m_run = m_new;
       l_run *= alpha;
+      lr_run *= alpha;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -185,6 +192,16 @@ __device__ __forceinline__ void fwd_pp_rows(const KArgs& a, const int bh, const 
       }
     l_run += psum;
     if constexpr (DROPOUT) {
+      // the normaliser sums the rounded probabilities before dropout
+      float part[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int cc = 0; cc < 4; ++cc) {
+        T8 all;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) all[t] = (T)s[cc >> 1][8 * (cc & 1) + t];
+        part[cc] = sum8(all, 0.f);
+      }
+      lr_run += (part[0] + part[1]) + (part[2] + part[3]);
       const KeepLQ kq = keep_tile_lane_query(k0, qi, bh, g, a.offset_lo, a.seed_lo, a.seed_hi, a.drop_thr);
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
@@ -198,42 +215,53 @@ __device__ __forceinline__ void fwd_pp_rows(const KArgs& a, const int bh, const 
     for (int cc = 0; cc < 4; ++cc)
 #pragma unroll
       for (int t = 0; t < 8; ++t) pf[cc][t] = (T)s[cc >> 1][8 * (cc & 1) + t];
+    if constexpr (!DROPOUT) {
+      float part[4];
+#pragma unroll
+      for (int cc = 0; cc < 4; ++cc) part[cc] = sum8(pf[cc], 0.f);
+      lr_run += (part[0] + part[1]) + (part[2] + part[3]);
+    }
   };
 
-  // ---- prologue: A copies K(0); B, which starts one block later, copies V(0) in slot 0
-  if (!group_b) dma.copy_rows(Kg, a.sn, 0, a.N, Ks[0]);
+  // ring slot of a tile in this group's ring
+  auto ring = [&](int slot) -> T* { return group_b ? Vs[slot] : Ks[slot]; };
+  // ---- prologue: tile 0 of this group's tensor.  Group B starts one block later (an extra
+  // barrier).  The wait also covers the Q fragment loads issued before.
+  dma.copy_rows(Tg, a.sn, 0, a.N, ring(0));
+  wait_async_copies();
   __syncthreads();
   if (group_b) {
-    dma.copy_rows(Vg, a.sn, 0, a.N, Vs[0]);
     __builtin_amdgcn_sched_barrier(0);
     __syncthreads();   // B runs one block behind A
   }
 
+  int cur = 0;   // ring slot of tile j: j % 3
   for (int j = 0; j < J; ++j) {
-    // ---- M(j): matrix work only
-    do_M(j > 0 && active(j - 1), j - 1, active(j), j);
+    const int nxt = cur == 2 ? 0 : cur + 1, prv = cur == 0 ? 2 : cur - 1;   // slots of tiles j + 1, j - 1
+    // ---- M(j): matrix work, then the copy of this group's tile j + 1 (its slot held tile j - 2)
+    do_M(j > 0 && active(j - 1), Vs[prv], active(j), Ks[cur]);
     __builtin_amdgcn_sched_barrier(0);
+    if (j + 1 < J) dma.copy_rows(Tg, a.sn, (j + 1) * BC, a.N, ring(nxt));
     __syncthreads();
     __builtin_amdgcn_sched_barrier(0);
-    // ---- X(j): start the copy of the next tile, then the online softmax
-    if (j + 1 < J) {
-      if (!group_b) dma.copy_rows(Kg, a.sn, (j + 1) * BC, a.N, Ks[(j + 1) & 1]);
-      else dma.copy_rows(Vg, a.sn, (j + 1) * BC, a.N, Vs[(j + 1) & 1]);
-    }
+    // ---- X(j): the online softmax; then tile j + 1 must have landed
     if (active(j)) do_softmax(j);
     __builtin_amdgcn_sched_barrier(0);
-    __syncthreads();   // also waits for this wavefront's copies
+    wait_async_copies();
+    __syncthreads();
     __builtin_amdgcn_sched_barrier(0);
+    cur = nxt;
   }
-  do_M(active(J - 1), J - 1, false, 0);
+  do_M(active(J - 1), Vs[cur == 0 ? 2 : cur - 1], false, Ks[0]);
   if (!group_b) { __builtin_amdgcn_sched_barrier(0); __syncthreads(); }  // equal barrier counts
   __builtin_amdgcn_sched_barrier(0);
   __syncthreads();   // every wavefront is done with the tiles: the buffers become output staging
 
   if (!valid) return;
   const float l_sum = l_run + xchg32(l_run);
+  const float lr_sum = lr_run + xchg32(lr_run);
   const float l_tot = qi < len ? l_sum : 0.f;   // padding rows: O = 0, LSE = -inf
-  const float inv = l_tot > 0.f ? (DROPOUT ? a.keep_scale : 1.f) / l_tot : 0.f;
+  const float inv = (l_tot > 0.f && lr_sum > 0.f) ? (DROPOUT ? a.keep_scale : 1.f) / lr_sum : 0.f;
   if (g == 0 && row_ok) {
     const float lse = l_tot > 0.f ? (m_run + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f : -INFINITY;
     a.LSE[(int64_t)bh * a.N + qi] = lse;
@@ -262,8 +290,8 @@ __device__ __forceinline__ void fwd_pp_rows(const KArgs& a, const int bh, const 
 // and the static assignment of items to compute units stays balanced.
 template <typename T, int D, bool CAUSAL, bool DROPOUT>
 __global__ __launch_bounds__(NT) void fwd_pp_kernel(const KArgs a) {
-  __shared__ __attribute__((aligned(16))) T Ks[2][BC * D];
-  __shared__ __attribute__((aligned(16))) T Vs[2][BC * D];
+  __shared__ __attribute__((aligned(16))) T Ks[3][BC * D];
+  __shared__ __attribute__((aligned(16))) T Vs[3][BC * D];
   const int item = xcd_item(a.n_items, a.chunk);
   if (item < 0) return;
   const int n_qt = (a.N + BRW - 1) / BRW;
