@@ -170,7 +170,7 @@ def run_gpu(cfg, steps, warmup, seed, mask_override=None, nsets=1):
     if cfg["sparse"]:
         use_pp = False
     else:
-        use_pp = d == 128 and (cfg["p"] > 0 or N >= 512)
+        use_pp = d == 128 and (cfg["p"] > 0 or N >= 1024 or (cfg["causal"] and N >= 512))
     names = ["fwd_pp_kernel" if use_pp else "fwd_kernel", "rowdot_kernel", "dq_kernel", "dkv_rs_kernel"]
     per_step = {n: [] for n in names}
     for e in evs:

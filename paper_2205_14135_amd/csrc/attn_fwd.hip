@@ -337,16 +337,18 @@ __global__ void dropout_mask_kernel(const KArgs a, uint8_t* keep) {
 }  // namespace
 
 int launch_fwd(const KArgs& a, int dtype, int d, bool causal, bool dropout, bool sparse, hipStream_t s) {
-  // Dense d = 128 problems take the two-group ping-pong kernel (attn_fwd_pp.hip) from N = 512 on
-  // (and always with dropout): there the matrix blocks are long enough for the MFMA / softmax
-  // overlap to pay.  At d = 64 the vector ALU work dominates and two free-running workgroups
+  // Dense d = 128 problems take the two-group ping-pong kernel (attn_fwd_pp.hip) from N = 1024 on
+  // (from 512 under the causal mask, where its paired work items balance better, and always with
+  // dropout): there the matrix blocks are long enough for the MFMA / softmax overlap to pay
+  // (measured: 4-6 % faster than this file's kernel from N = 2048, equal at 1024, 6 % slower at
+  // 512 without a mask).  At d = 64 the vector ALU work dominates and two free-running workgroups
   // per compute unit (this file) measured faster at every N; block-sparse problems always take
   // this kernel.  ATTN_FWD_VARIANT=base|pp overrides the choice (bench-time comparison).
   static const char variant = [] {
     const char* v = getenv("ATTN_FWD_VARIANT");
     return v != nullptr ? v[0] : 'a';
   }();
-  bool use_pp = d == 128 && (dropout || a.N >= 512);
+  bool use_pp = d == 128 && (dropout || a.N >= 1024 || (causal && a.N >= 512));
   if (variant == 'b') use_pp = false;
   if (variant == 'p' && d != 32) use_pp = true;
   if (!sparse && use_pp) return launch_fwd_pp(a, dtype, d, causal, dropout, s);
