@@ -104,3 +104,29 @@ def test_mfma_rate_probe_runs_and_reports_its_flops():
         assert flops == 2.0 * 32 * 32 * 16 * 4 * 100 * 4 * 2048
     torch.cuda.synchronize()
     assert float(sink.abs().sum()) == 0.0      # the sink is never written
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("d,dtype", [(64, "bf16"), (128, "bf16"), (128, "fp16")])
+@pytest.mark.parametrize("step", [0.02, 0.4, 3.0])
+def test_logits_that_grow_along_the_keys(d, dtype, step):
+    """The row maximum moves on every key tile: by a little (the softmax reference of the kernels then
+    lags behind it for many tiles), by about its rescale threshold per tile, or by far more (a rescale
+    on every tile).  Keys are a fixed direction scaled by the key index plus noise, so S_ij rises by
+    about `step` per key (in units of the scaled logit).  Forward only: the backward kernels take the
+    saved statistic L, checked here, and never see the reference."""
+    B, H, N = 1, 2, 1024
+    rng = np.random.default_rng(inputs.BASE_SEED + 1400 + d)
+    u = rng.standard_normal(d)
+    u /= np.linalg.norm(u)
+    tau = 1 / math.sqrt(d)
+    q = np.tile(u, (B, H, N, 1)) * 4.0 + 0.3 * rng.standard_normal((B, H, N, d))
+    ramp = (np.arange(N) * step / (4.0 * tau))[None, None, :, None]
+    k = u[None, None, None, :] * ramp + 0.3 * rng.standard_normal((B, H, N, d))
+    v = rng.standard_normal((B, H, N, d))
+    t = {n: inputs.round_to(x.astype(np.float32), dtype) for n, x in (("Q", q), ("K", k), ("V", v))}
+    dev = {n: inputs.to_torch(x, dtype, "cuda") for n, x in t.items()}
+    for causal in (False, True):
+        res = hp.check_forward(t, dev, dtype, tau, causal=causal)
+        print(d, dtype, step, causal, res)
+        hp.assert_forward_ok(res)
