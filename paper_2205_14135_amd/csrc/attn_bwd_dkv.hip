@@ -23,6 +23,8 @@
 #include "attn_common.h"
 #include "attn_tiles.h"
 
+#include <cstdlib>
+
 namespace attn {
 namespace {
 
@@ -479,6 +481,14 @@ int launch_td(KArgs a, bool causal, bool dropout, bool sparse, hipStream_t s) {
 }  // namespace
 
 int launch_dkv_rs(const KArgs& a, int dtype, int d, bool causal, bool dropout, bool sparse, hipStream_t s) {
+  // Dense problems with d <= 64 take the kernel in which one wavefront does all four products
+  // (attn_bwd_dkv_fr.hip).  ATTN_DKV_VARIANT=rs|fr overrides the choice (bench-time comparison;
+  // fr exists for d <= 64 only).
+  static const char variant = [] {
+    const char* v = getenv("ATTN_DKV_VARIANT");
+    return v != nullptr ? v[0] : 'a';
+  }();
+  if (!sparse && d <= 64 && variant != 'r') return launch_dkv_fr(a, dtype, d, causal, dropout, s);
   if (dtype == 0 && d == 32) return launch_td<_Float16, 32>(a, causal, dropout, sparse, s);
   if (dtype == 1 && d == 32) return launch_td<__bf16, 32>(a, causal, dropout, sparse, s);
   if (dtype == 0 && d == 64) return launch_td<_Float16, 64>(a, causal, dropout, sparse, s);

@@ -1,0 +1,295 @@
+// dK / dV kernel for head dimensions up to 64, dense problems: one wavefront does all four tile
+// products of its 32 keys.
+//
+// Arithmetic: Algorithm 4 of the paper for one block of 128 keys, swept over 64-query tiles:
+//     S = Q K^T, P = exp(S - L), dV += (P o Z)^T dO, dP = (dO V^T) o Z, dS = P o (dP - D), dK += tau dS^T Q.
+// At d <= 64 both accumulators (dK^T, dV^T), both operand fragment sets (K, V) and the S / dP tiles
+// of a wavefront fit in 256 registers, so the work of a key block need not be split over two
+// wavefronts of a SIMD as in attn_bwd_dkv.hip: no probabilities travel through LDS, there is one
+// workgroup barrier per tile (for the tile buffers only), and a workgroup is 4 wavefronts, so two
+// or more independent workgroups share a compute unit and fill each other's stalls.  The vector
+// ALU work per tile is the same at every head dimension while the matrix work shrinks with it;
+// at d <= 64 that free-running arrangement is faster than the role split (which wins at d = 128,
+// where it is also the only one that fits the register file).
+// Register layout "lane = key" (S = Q K^T: accumulator rows = queries of the tile, column = the
+// lane's key), as in attn_bwd_dkv.hip.
+#include "attn_common.h"
+#include "attn_tiles.h"
+
+namespace attn {
+namespace {
+
+constexpr int NT = 256;
+constexpr int TILE = 64;
+
+template <typename T, int D, bool CAUSAL, bool DROPOUT>
+__global__ __launch_bounds__(NT, 2) void dkv_fr_kernel(const KArgs a) {
+  typedef typename Vec<T>::x8 T8;
+  constexpr int KK = D / 16, DB = D / 32;
+  static_assert(D <= 64, "the accumulators of both gradients must fit one wavefront");
+  __shared__ __attribute__((aligned(16))) T Qs[2][TILE * D];
+  __shared__ __attribute__((aligned(16))) T Gs[2][TILE * D];      // dO tiles
+  __shared__ __attribute__((aligned(16))) float Ls[2][TILE];      // base-2 row statistic
+  __shared__ __attribute__((aligned(16))) float Ds[2][TILE];      // -D_i
+
+  const int n_kt = a.T;   // ceil(N / 128): the last key block may be ragged
+  // Work assignment: one key block per workgroup; under the causal mask key block k is visited by
+  // N/64 - 2k query tiles, so a workgroup takes the pair (k, n_kt - 1 - k), one per round.
+  const int n_pair = (n_kt + 1) / 2;
+  const int item0 = xcd_item(a.n_items, a.chunk);
+  if (item0 < 0) return;
+  for (int round = 0;; ++round) {
+  int item = item0;
+  bool last_round = true;
+  if constexpr (CAUSAL) {
+    const int q = item % n_pair;
+    last_round = round == 1 || q == n_kt - 1 - q;
+    item = (item / n_pair) * n_kt + (round == 0 ? q : n_kt - 1 - q);
+  }
+  const int bh = item / n_kt;
+  const int kt = item % n_kt;
+  const int b = bh / a.H, h = bh % a.H;
+  const int64_t head_off = (int64_t)b * a.sb + (int64_t)h * a.sh;
+  const T* __restrict__ Qg = (const T*)a.Q + head_off;
+  const T* __restrict__ Gg = (const T*)a.dO + head_off;
+  // padded to a multiple of 128 rows per head: +inf / 0 beyond a ragged end, so those query rows
+  // (whose Q and dO tile rows are copies of the last real row) contribute P = 0 and dS = 0
+  const float* __restrict__ Lg = a.L2vec + (int64_t)bh * a.Nr;
+  const float* __restrict__ Dg = a.Dvec + (int64_t)bh * a.Nr;
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = lane & 31, g = lane >> 5;
+  const int kw0 = kt * 128 + wave * 32;
+  const int kj = kw0 + r;  // this lane's key (>= N beyond a ragged end: masked like a padded key, never stored)
+
+  // loop-invariant B operands: the K and V fragments of this lane's key
+  T8 kf[KK], vf[KK];
+  {
+    const int64_t row_off = head_off + (int64_t)min(kj, a.N - 1) * a.sn;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      kf[kk] = *(const T8*)((const T*)a.K + row_off + 16 * kk + 8 * g);
+      vf[kk] = *(const T8*)((const T*)a.V + row_off + 16 * kk + 8 * g);
+    }
+  }
+  // The fragments must have arrived before the tile loop: a wait for them inside the loop would
+  // also wait for the asynchronous tile copies in flight there.
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+  f32x16 dv[DB], dk[DB];   // dV^T, dK^T (rows d, column = this lane's key)
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { dv[db][i] = 0.f; dk[db][i] = 0.f; }
+
+  // key-padding mask: key blocks and query tiles at or beyond the batch's length are not visited
+  // (rows >= len inside the last tile have LSE = -inf, hence P = 0); masked keys get P = 0
+  const int len = a.klen ? min(max(a.klen[b], 0), a.N) : a.N;
+  const int first = CAUSAL ? 2 * kt : 0;
+  const int limit = kt * 128 >= len ? 0 : (len + TILE - 1) / TILE;   // len <= N
+
+  TrOffsets<D> tro;
+  tro.init();
+  TileAsync<T, D, 4> dma;
+  dma.init(a.sn, wave);
+  auto fetch_tile = [&](int t, int buf) {
+    dma.copy_rows(Qg, a.sn, t * TILE, a.N, Qs[buf]);
+    dma.copy_rows(Gg, a.sn, t * TILE, a.N, Gs[buf]);
+    if (wave == 1) async_copy_b32(Lg + t * TILE + lane, __builtin_amdgcn_readfirstlane(lds_addr(Ls[buf])));
+    if (wave == 2) async_copy_b32(Dg + t * TILE + lane, __builtin_amdgcn_readfirstlane(lds_addr(Ds[buf])));
+  };
+  const float c = a.scale_log2;
+
+  // LDS operand reads run PF fragments ahead of the MFMA that consumes them
+  constexpr int PF = 4;
+  // out[qb] = Tile[32 qb .. +31][:] . frags  (cinit: 64 per-row start values, nullptr = zero)
+  auto row_product = [&](const T* tile, const T8 (&bfrag)[KK], const float* cinit, f32x16 (&out)[2]) {
+    auto frag = [&](int f) { return *(const T8*)(tile + lds_off<D>(32 * (f & 1) + r, 2 * (f >> 1) + g)); };  // f = 2 kk + qb
+    T8 ring[PF];
+#pragma unroll
+    for (int f = 0; f < PF; ++f) ring[f] = frag(f);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int f = 0; f < 2 * KK; ++f) {
+      const T8 cur = ring[f % PF];
+      if (f < 2) {
+        f32x16 z;
+        if (cinit != nullptr) {
+#pragma unroll
+          for (int i4 = 0; i4 < 4; ++i4) {
+            const f32x4 c4 = *(const f32x4*)(cinit + 32 * f + 8 * i4 + 4 * g);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) z[4 * i4 + e] = c4[e];
+          }
+        } else {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) z[i] = 0.f;
+        }
+        out[f & 1] = mfma32(cur, bfrag[f >> 1], z);
+      } else {
+        out[f & 1] = mfma32(cur, bfrag[f >> 1], out[f & 1]);
+      }
+      if (f + PF < 2 * KK) ring[f % PF] = frag(f + PF);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  // acc^T += Tile^T . frag   (contraction over the 64 queries of the tile)
+  auto col_product = [&](const T* tile, const T8 (&bfrag)[4], f32x16 (&acc)[DB]) {
+    auto frag = [&](int f) {   // f = DB cc + db: consecutive MFMAs hit different accumulators
+      const T* base = tile + 16 * (f / DB) * D;
+      return tr_frag<T8>(base + tro.off[f % DB][0], base + tro.off[f % DB][1]);
+    };
+    T8 ring[PF];
+#pragma unroll
+    for (int f = 0; f < PF; ++f) ring[f] = frag(f);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int f = 0; f < 4 * DB; ++f) {
+      const T8 cur = ring[f % PF];
+      acc[f % DB] = mfma32(cur, bfrag[f / DB], acc[f % DB]);
+      if (f + PF < 4 * DB) ring[f % PF] = frag(f + PF);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  // Dropout bits in this layout (same scheme as attn_bwd_dkv.hip).  A draw decides eight
+  // consecutive keys of one query row, i.e. the eight lanes r = 8 m .. 8 m + 7 of one half-wave;
+  // lane u = r % 8 draws the four rows (qb = u / 4, i4 = 0..3, e = u % 4), and the group exchanges
+  // the words by DPP so that kw[qb][e] bit 8 i4 is this lane's key for row (qb, i4, e).
+  auto keep_words = [&](uint32_t mine, uint32_t (&kw)[2][4]) {
+    const int u = r & 7;
+    const uint32_t mirrored = (uint32_t)__builtin_amdgcn_mov_dpp((int)mine, 0x141, 0xF, 0xF, true);   // row_half_mirror
+    uint32_t own[4], oth[4];
+    own[0] = (uint32_t)__builtin_amdgcn_mov_dpp((int)mine, 0x00, 0xF, 0xF, true);
+    own[1] = (uint32_t)__builtin_amdgcn_mov_dpp((int)mine, 0x55, 0xF, 0xF, true);
+    own[2] = (uint32_t)__builtin_amdgcn_mov_dpp((int)mine, 0xAA, 0xF, 0xF, true);
+    own[3] = (uint32_t)__builtin_amdgcn_mov_dpp((int)mine, 0xFF, 0xF, 0xF, true);
+    oth[3] = (uint32_t)__builtin_amdgcn_mov_dpp((int)mirrored, 0x00, 0xF, 0xF, true);
+    oth[2] = (uint32_t)__builtin_amdgcn_mov_dpp((int)mirrored, 0x55, 0xF, 0xF, true);
+    oth[1] = (uint32_t)__builtin_amdgcn_mov_dpp((int)mirrored, 0xAA, 0xF, 0xF, true);
+    oth[0] = (uint32_t)__builtin_amdgcn_mov_dpp((int)mirrored, 0xFF, 0xF, 0xF, true);
+    const bool upper = (u & 4) != 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      kw[0][e] = (upper ? oth[e] : own[e]) >> u;
+      kw[1][e] = (upper ? own[e] : oth[e]) >> u;
+    }
+  };
+  auto draw_keep = [&](int i0) {
+    uint32_t mine = 0;
+    const int u = r & 7;
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+      const uint32_t qrow = (uint32_t)(i0 + 32 * (u >> 2) + 8 * m + 4 * g + (u & 3));
+      mine |= philox_keep8((uint32_t)kj >> 3, qrow, (uint32_t)bh, a.offset_lo, a.seed_lo, a.seed_hi, a.drop_thr) << (8 * m);
+    }
+    return mine;
+  };
+
+  // ---- pipeline over the query tiles of this key block: tile t + 1 streams in while t is used
+  int buf = 0;
+  if (first < limit) fetch_tile(first, 0);
+  wait_async_copies();
+  __syncthreads();
+  for (int t = first; t < limit; ++t) {
+    if (t + 1 < limit) fetch_tile(t + 1, buf ^ 1);
+    const int i0 = t * TILE;
+    if (!CAUSAL || i0 + TILE - 1 >= kw0) {
+      f32x16 s[2], dp[2];
+      row_product(Qs[buf], kf, nullptr, s);                 // S = Q K^T
+      uint32_t kw[2][4] = {{0, 0, 0, 0}, {0, 0, 0, 0}};
+      if constexpr (DROPOUT) keep_words(draw_keep(i0), kw);
+      if (kw0 + 32 > len) {   // this wavefront holds padded keys: their logits become -inf, hence P = 0
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+          for (int i = 0; i < 16; ++i)
+            if (kj >= len) s[qb][i] = -INFINITY;
+      }
+      // P = exp(S - L), kept in fp32 in s[] for dS; the 16-bit (dropped) copy feeds dV
+      T8 pf[4];
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+          const f32x4 l4 = *(const f32x4*)(&Ls[buf][32 * qb + 8 * i4 + 4 * g]);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int i = 4 * i4 + e;
+            float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[qb][i], c, -l4[e]));
+            if (CAUSAL && kj > i0 + 32 * qb + 8 * i4 + 4 * g + e) p = 0.f;
+            s[qb][i] = p;
+            const int cc = 2 * qb + (i4 >> 1), tt = 4 * (i4 & 1) + e;
+            if constexpr (DROPOUT) {
+              const bool keep = (kw[qb][e] >> (8 * i4)) & 1u;
+              pf[cc][tt] = (T)(keep ? p : 0.f);
+            } else {
+              pf[cc][tt] = (T)p;
+            }
+          }
+        }
+      col_product(Gs[buf], pf, dv);                          // dV^T += dO^T P_dropped
+      // dP = dO V^T; without dropout it starts from -D, so the result is dP - D
+      row_product(Gs[buf], vf, DROPOUT ? nullptr : Ds[buf], dp);
+      T8 dsf[4];
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+          f32x4 d4 = {0.f, 0.f, 0.f, 0.f};
+          if constexpr (DROPOUT) d4 = *(const f32x4*)(&Ds[buf][32 * qb + 8 * i4 + 4 * g]);   // -D_i
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int i = 4 * i4 + e;
+            const int cc = 2 * qb + (i4 >> 1), tt = 4 * (i4 & 1) + e;
+            float dpv = dp[qb][i];
+            if constexpr (DROPOUT) {
+              const bool keep = (kw[qb][e] >> (8 * i4)) & 1u;
+              dpv = (keep ? dpv * a.keep_scale : 0.f) + d4[e];
+            }
+            dsf[cc][tt] = (T)(s[qb][i] * dpv);
+          }
+        }
+      col_product(Qs[buf], dsf, dk);                         // dK^T += Q^T dS
+    }
+    wait_async_copies();
+    __syncthreads();   // the next tile has landed, and everyone is done with this buffer
+    buf ^= 1;
+  }
+
+  // the loop ends on a barrier (or never touched LDS): the tile buffers stage the output rows
+  {
+    T* stage_v = &Qs[0][0] + wave * 32 * D;   // 4 wavefronts x 32 rows = the two Q buffers
+    T* stage_k = &Gs[0][0] + wave * 32 * D;
+    store_rows_coalesced<T, D>(stage_v, (T*)a.dV + head_off + (int64_t)kw0 * a.sn, a.sn, dv,
+                               DROPOUT ? a.keep_scale : 1.f, a.N - kw0);
+    store_rows_coalesced<T, D>(stage_k, (T*)a.dK + head_off + (int64_t)kw0 * a.sn, a.sn, dk, a.tau, a.N - kw0);
+  }
+  if (last_round) return;
+  __syncthreads();   // LDS is reused by the next key block
+  }  // for round
+}
+
+template <typename T, int D>
+int launch_td(KArgs a, bool causal, bool dropout, hipStream_t s) {
+  if (causal) {   // items are pairs of key blocks
+    a.n_items = a.B * a.H * ((a.T + 1) / 2);
+    a.chunk = (a.n_items + kXcds - 1) / kXcds;
+  }
+  const dim3 grid(kXcds * a.chunk), block(NT);
+  if (!causal && !dropout) hipLaunchKernelGGL((dkv_fr_kernel<T, D, false, false>), grid, block, 0, s, a);
+  else if (causal && !dropout) hipLaunchKernelGGL((dkv_fr_kernel<T, D, true, false>), grid, block, 0, s, a);
+  else if (!causal && dropout) hipLaunchKernelGGL((dkv_fr_kernel<T, D, false, true>), grid, block, 0, s, a);
+  else hipLaunchKernelGGL((dkv_fr_kernel<T, D, true, true>), grid, block, 0, s, a);
+  return (int)hipGetLastError();
+}
+
+}  // namespace
+
+int launch_dkv_fr(const KArgs& a, int dtype, int d, bool causal, bool dropout, hipStream_t s) {
+  if (dtype == 0 && d == 32) return launch_td<_Float16, 32>(a, causal, dropout, s);
+  if (dtype == 1 && d == 32) return launch_td<__bf16, 32>(a, causal, dropout, s);
+  if (dtype == 0 && d == 64) return launch_td<_Float16, 64>(a, causal, dropout, s);
+  if (dtype == 1 && d == 64) return launch_td<__bf16, 64>(a, causal, dropout, s);
+  return (int)hipErrorInvalidValue;
+}
+
+}  // namespace attn
