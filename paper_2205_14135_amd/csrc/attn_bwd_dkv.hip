@@ -24,6 +24,7 @@
 #include "attn_tiles.h"
 
 #include <cstdlib>
+#include <type_traits>
 
 namespace attn {
 namespace {
@@ -440,6 +441,15 @@ __global__ __launch_bounds__(256) void sparse_finish_kernel(const KArgs a) {
   }
 }
 
+// ATTN_DKV_VARIANT=rs keeps the role-split kernel at every head dimension (bench-time comparison)
+bool force_role_split() {
+  static const bool forced = [] {
+    const char* v = getenv("ATTN_DKV_VARIANT");
+    return v != nullptr && v[0] == 'r';
+  }();
+  return forced;
+}
+
 template <typename T, int D>
 int launch_td(KArgs a, bool causal, bool dropout, bool sparse, hipStream_t s) {
   const int cols = a.B * a.H * a.T;
@@ -454,6 +464,15 @@ int launch_td(KArgs a, bool causal, bool dropout, bool sparse, hipStream_t s) {
   if (causal && !sparse) {   // items are pairs of key blocks
     a.n_items = a.B * a.H * ((a.T + 1) / 2);
     a.chunk = (a.n_items + kXcds - 1) / kXcds;
+  }
+  if (sparse && D <= 64 && !force_role_split()) {
+    // d <= 64: the kernel in which one wavefront does all four products, same work assignment
+    int e = launch_dkv_fr(a, std::is_same<T, __bf16>::value ? 1 : 0, D, causal, dropout, true, kListGroups, s);
+    if (e == 0) {
+      hipLaunchKernelGGL((sparse_finish_kernel<T, D>), dim3(cols), dim3(256), 0, s, a);
+      e = (int)hipGetLastError();
+    }
+    return e;
   }
   const dim3 grid(kXcds * a.chunk + (sparse ? kListGroups : 0)), block(NT);
 #define ATTN_DKV_CASE(C, P, S)                                                    \
@@ -481,14 +500,10 @@ int launch_td(KArgs a, bool causal, bool dropout, bool sparse, hipStream_t s) {
 }  // namespace
 
 int launch_dkv_rs(const KArgs& a, int dtype, int d, bool causal, bool dropout, bool sparse, hipStream_t s) {
-  // Dense problems with d <= 64 take the kernel in which one wavefront does all four products
-  // (attn_bwd_dkv_fr.hip).  ATTN_DKV_VARIANT=rs|fr overrides the choice (bench-time comparison;
-  // fr exists for d <= 64 only).
-  static const char variant = [] {
-    const char* v = getenv("ATTN_DKV_VARIANT");
-    return v != nullptr ? v[0] : 'a';
-  }();
-  if (!sparse && d <= 64 && variant != 'r') return launch_dkv_fr(a, dtype, d, causal, dropout, s);
+  // Problems with d <= 64 take the kernel in which one wavefront does all four products
+  // (attn_bwd_dkv_fr.hip; the block-sparse ones from inside launch_td, between the column
+  // planning and the finish kernel).
+  if (!sparse && d <= 64 && !force_role_split()) return launch_dkv_fr(a, dtype, d, causal, dropout, false, 0, s);
   if (dtype == 0 && d == 32) return launch_td<_Float16, 32>(a, causal, dropout, sparse, s);
   if (dtype == 1 && d == 32) return launch_td<__bf16, 32>(a, causal, dropout, sparse, s);
   if (dtype == 0 && d == 64) return launch_td<_Float16, 64>(a, causal, dropout, sparse, s);

@@ -1,5 +1,5 @@
-// dK / dV kernel for head dimensions up to 64, dense problems: one wavefront does all four tile
-// products of its 32 keys.
+// dK / dV kernel for head dimensions up to 64 (dense and block-sparse): one wavefront does all
+// four tile products of its 32 keys.
 //
 // Arithmetic: Algorithm 4 of the paper for one block of 128 keys, swept over 64-query tiles:
 //     S = Q K^T, P = exp(S - L), dV += (P o Z)^T dO, dP = (dO V^T) o Z, dS = P o (dP - D), dK += tau dS^T Q.
@@ -22,7 +22,7 @@ namespace {
 constexpr int NT = 256;
 constexpr int TILE = 64;
 
-template <typename T, int D, bool CAUSAL, bool DROPOUT>
+template <typename T, int D, bool CAUSAL, bool DROPOUT, bool SPARSE>
 __global__ __launch_bounds__(NT, 2) void dkv_fr_kernel(const KArgs a) {
   typedef typename Vec<T>::x8 T8;
   constexpr int KK = D / 16, DB = D / 32;
@@ -33,18 +33,41 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr_kernel(const KArgs a) {
   __shared__ __attribute__((aligned(16))) float Ds[2][TILE];      // -D_i
 
   const int n_kt = a.T;   // ceil(N / 128): the last key block may be ragged
-  // Work assignment: one key block per workgroup; under the causal mask key block k is visited by
-  // N/64 - 2k query tiles, so a workgroup takes the pair (k, n_kt - 1 - k), one per round.
+  // Work assignment.  Dense: one key block per workgroup; under the causal mask key block k is
+  // visited by N/64 - 2k query tiles, so a workgroup takes the pair (k, n_kt - 1 - k), one per
+  // round.  Block-sparse (as in attn_bwd_dkv.hip): the first 8 * chunk workgroups take one mask
+  // column each and leave the heavy ones alone; those were cut into segments by
+  // sparse_plan_kernel and the remaining workgroups walk that segment list.
+  const int n_col_groups = kXcds * a.chunk;
+  const bool list_mode = SPARSE && (int)blockIdx.x >= n_col_groups;
+  constexpr bool PAIRED = CAUSAL && !SPARSE;
   const int n_pair = (n_kt + 1) / 2;
-  const int item0 = xcd_item(a.n_items, a.chunk);
-  if (item0 < 0) return;
   for (int round = 0;; ++round) {
-  int item = item0;
-  bool last_round = true;
-  if constexpr (CAUSAL) {
-    const int q = item % n_pair;
-    last_round = round == 1 || q == n_kt - 1 - q;
-    item = (item / n_pair) * n_kt + (round == 0 ? q : n_kt - 1 - q);
+  int item, skip_blocks = 0, take_blocks = 0x7fffffff;
+  bool heavy = false, last_round = true;
+  if (!list_mode) {
+    item = xcd_item(a.n_items, a.chunk);
+    if (item < 0) return;
+    if constexpr (SPARSE) {
+      if (a.colcnt[item] > a.seglist[2]) return;
+    }
+    if constexpr (PAIRED) {
+      const int q = item % n_pair;
+      last_round = round == 1 || q == n_kt - 1 - q;
+      item = (item / n_pair) * n_kt + (round == 0 ? q : n_kt - 1 - q);
+    }
+  } else {
+    const int idx = ((int)blockIdx.x - n_col_groups) + round * ((int)gridDim.x - n_col_groups);
+    if (idx >= a.seglist[0]) return;
+    const int e = a.seglist[kSegHeader + idx];
+    item = e / kMaxSegs;
+    const int seg = e % kMaxSegs;
+    const int cnt = a.colcnt[item];
+    const int nseg = min((int)kMaxSegs, (cnt + kSegBlocks - 1) / kSegBlocks);
+    const int seg_len = (cnt + nseg - 1) / nseg;
+    skip_blocks = seg * seg_len;
+    take_blocks = seg_len;
+    heavy = true;
   }
   const int bh = item / n_kt;
   const int kt = item % n_kt;
@@ -84,8 +107,12 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr_kernel(const KArgs a) {
   // key-padding mask: key blocks and query tiles at or beyond the batch's length are not visited
   // (rows >= len inside the last tile have LSE = -inf, hence P = 0); masked keys get P = 0
   const int len = a.klen ? min(max(a.klen[b], 0), a.N) : a.N;
-  const int first = CAUSAL ? 2 * kt : 0;
-  const int limit = kt * 128 >= len ? 0 : (len + TILE - 1) / TILE;   // len <= N
+  TileIter<SPARSE> it;
+  if constexpr (SPARSE)
+    it.init(a.mask + (int64_t)h * a.mask_sh + kt, a.T, CAUSAL ? kt : 0,
+            kt * 128 >= len ? 0 : min(a.T, (len + 127) / 128), skip_blocks, take_blocks);
+  else
+    it.init(nullptr, 0, CAUSAL ? 2 * kt : 0, kt * 128 >= len ? 0 : (len + TILE - 1) / TILE);   // len <= N
 
   TrOffsets<D> tro;
   tro.init();
@@ -186,11 +213,13 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr_kernel(const KArgs a) {
 
   // ---- pipeline over the query tiles of this key block: tile t + 1 streams in while t is used
   int buf = 0;
-  if (first < limit) fetch_tile(first, 0);
+  int t = it.next();
+  if (t >= 0) fetch_tile(t, 0);
   wait_async_copies();
   __syncthreads();
-  for (int t = first; t < limit; ++t) {
-    if (t + 1 < limit) fetch_tile(t + 1, buf ^ 1);
+  while (t >= 0) {
+    const int t_next = it.next();
+    if (t_next >= 0) fetch_tile(t_next, buf ^ 1);
     const int i0 = t * TILE;
     if (!CAUSAL || i0 + TILE - 1 >= kw0) {
       f32x16 s[2], dp[2];
@@ -253,42 +282,69 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr_kernel(const KArgs a) {
     wait_async_copies();
     __syncthreads();   // the next tile has landed, and everyone is done with this buffer
     buf ^= 1;
+    t = t_next;
   }
 
-  // the loop ends on a barrier (or never touched LDS): the tile buffers stage the output rows
-  {
+  if (SPARSE && heavy) {
+    // one of several segments of this column: sum in fp32; sparse_finish_kernel converts
+    float* dst_v = a.dVacc + ((int64_t)bh * a.N + kj) * D;
+    float* dst_k = a.dKacc + ((int64_t)bh * a.N + kj) * D;
+    const float sv = DROPOUT ? a.keep_scale : 1.f;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int col = 32 * db + 8 * (i >> 2) + 4 * g + (i & 3);
+        unsafeAtomicAdd(dst_v + col, dv[db][i] * sv);
+        unsafeAtomicAdd(dst_k + col, dk[db][i] * a.tau);
+      }
+  } else {
+    // the loop ends on a barrier (or never touched LDS): the tile buffers stage the output rows
     T* stage_v = &Qs[0][0] + wave * 32 * D;   // 4 wavefronts x 32 rows = the two Q buffers
     T* stage_k = &Gs[0][0] + wave * 32 * D;
     store_rows_coalesced<T, D>(stage_v, (T*)a.dV + head_off + (int64_t)kw0 * a.sn, a.sn, dv,
                                DROPOUT ? a.keep_scale : 1.f, a.N - kw0);
     store_rows_coalesced<T, D>(stage_k, (T*)a.dK + head_off + (int64_t)kw0 * a.sn, a.sn, dk, a.tau, a.N - kw0);
   }
-  if (last_round) return;
+  if (!list_mode && last_round) return;
   __syncthreads();   // LDS is reused by the next key block
   }  // for round
 }
 
 template <typename T, int D>
-int launch_td(KArgs a, bool causal, bool dropout, hipStream_t s) {
-  if (causal) {   // items are pairs of key blocks
+int launch_td(KArgs a, bool causal, bool dropout, bool sparse, int extra_groups, hipStream_t s) {
+  if (causal && !sparse) {   // items are pairs of key blocks
     a.n_items = a.B * a.H * ((a.T + 1) / 2);
     a.chunk = (a.n_items + kXcds - 1) / kXcds;
   }
-  const dim3 grid(kXcds * a.chunk), block(NT);
-  if (!causal && !dropout) hipLaunchKernelGGL((dkv_fr_kernel<T, D, false, false>), grid, block, 0, s, a);
-  else if (causal && !dropout) hipLaunchKernelGGL((dkv_fr_kernel<T, D, true, false>), grid, block, 0, s, a);
-  else if (!causal && dropout) hipLaunchKernelGGL((dkv_fr_kernel<T, D, false, true>), grid, block, 0, s, a);
-  else hipLaunchKernelGGL((dkv_fr_kernel<T, D, true, true>), grid, block, 0, s, a);
-  return (int)hipGetLastError();
+  const dim3 grid(kXcds * a.chunk + (sparse ? extra_groups : 0)), block(NT);
+#define ATTN_DKV_FR_CASE(C, P, S)                                                     \
+  if (causal == C && dropout == P && sparse == S) {                                   \
+    hipLaunchKernelGGL((dkv_fr_kernel<T, D, C, P, S>), grid, block, 0, s, a);         \
+    return (int)hipGetLastError();                                                    \
+  }
+  ATTN_DKV_FR_CASE(false, false, false)
+  ATTN_DKV_FR_CASE(true, false, false)
+  ATTN_DKV_FR_CASE(false, true, false)
+  ATTN_DKV_FR_CASE(true, true, false)
+  ATTN_DKV_FR_CASE(false, false, true)
+  ATTN_DKV_FR_CASE(true, false, true)
+  ATTN_DKV_FR_CASE(false, true, true)
+  ATTN_DKV_FR_CASE(true, true, true)
+#undef ATTN_DKV_FR_CASE
+  return (int)hipErrorInvalidValue;
 }
 
 }  // namespace
 
-int launch_dkv_fr(const KArgs& a, int dtype, int d, bool causal, bool dropout, hipStream_t s) {
-  if (dtype == 0 && d == 32) return launch_td<_Float16, 32>(a, causal, dropout, s);
-  if (dtype == 1 && d == 32) return launch_td<__bf16, 32>(a, causal, dropout, s);
-  if (dtype == 0 && d == 64) return launch_td<_Float16, 64>(a, causal, dropout, s);
-  if (dtype == 1 && d == 64) return launch_td<__bf16, 64>(a, causal, dropout, s);
+// sparse: the caller (attn_bwd_dkv.hip) has run the column count / plan kernels and runs the
+// finish kernel afterwards; extra_groups workgroups walk the list of heavy-column segments.
+int launch_dkv_fr(const KArgs& a, int dtype, int d, bool causal, bool dropout, bool sparse, int extra_groups,
+                  hipStream_t s) {
+  if (dtype == 0 && d == 32) return launch_td<_Float16, 32>(a, causal, dropout, sparse, extra_groups, s);
+  if (dtype == 1 && d == 32) return launch_td<__bf16, 32>(a, causal, dropout, sparse, extra_groups, s);
+  if (dtype == 0 && d == 64) return launch_td<_Float16, 64>(a, causal, dropout, sparse, extra_groups, s);
+  if (dtype == 1 && d == 64) return launch_td<__bf16, 64>(a, causal, dropout, sparse, extra_groups, s);
   return (int)hipErrorInvalidValue;
 }
 

@@ -63,7 +63,8 @@ int launch_dropout_mask(const KArgs& a, uint8_t* keep, hipStream_t s);
 // dK/dV kernel with the S->P->dV and dP->dS->dK halves on two wavefronts of a SIMD (attn_bwd_dkv.hip)
 int launch_dkv_rs(const KArgs& a, int dtype, int d, bool causal, bool dropout, bool sparse, hipStream_t s);
 // dense dK/dV kernel for d <= 64: one wavefront does all four tile products (attn_bwd_dkv_fr.hip)
-int launch_dkv_fr(const KArgs& a, int dtype, int d, bool causal, bool dropout, hipStream_t s);
+int launch_dkv_fr(const KArgs& a, int dtype, int d, bool causal, bool dropout, bool sparse, int extra_groups,
+                  hipStream_t s);
 // dense forward with two wavefront groups in ping-pong (attn_fwd_pp.hip); sets its own work items
 int launch_fwd_pp(const KArgs& a, int dtype, int d, bool causal, bool dropout, hipStream_t s);
 // MFMA-only kernel for measuring the sustained matrix rate (attn_probe.hip); *flops = FLOPs launched
