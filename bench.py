@@ -171,7 +171,9 @@ def run_gpu(cfg, steps, warmup, seed, mask_override=None, nsets=1):
         use_pp = False
     else:
         use_pp = d == 128 and (cfg["p"] > 0 or N >= 1024 or (cfg["causal"] and N >= 512))
-    names = ["fwd_pp_kernel" if use_pp else "fwd_kernel", "rowdot_kernel", "dq_kernel", "dkv_rs_kernel"]
+    # dK/dV: the one-wavefront kernel at d <= 64, the role-split one at d = 128 (launch_dkv_rs())
+    names = ["fwd_pp_kernel" if use_pp else "fwd_kernel", "rowdot_kernel", "dq_kernel",
+             "dkv_fr_kernel" if d <= 64 else "dkv_rs_kernel"]
     per_step = {n: [] for n in names}
     for e in evs:
         for i, n in enumerate(names):
