@@ -165,9 +165,10 @@ int attn_blocksparse_bwd(const attn_params* p, const uint8_t* block_mask, int32_
 /*
  * Profiling aid for the backward pass (Algorithm 4 as attn_bwd / attn_blocksparse_bwd run it):
  * identical to attn_bwd when block_mask is NULL and to attn_blocksparse_bwd otherwise, and in
- * addition records the caller's four hipEvent_t handles on p->stream: events[0] before the first
- * launch, events[1] after the row-dot kernel (D = rowsum(dO o O)), events[2] after the dQ kernel,
- * events[3] after the dK/dV kernel.  The events stay owned by the caller.
+ * addition records the caller's four hipEvent_t handles on p->stream: events[0] and events[1]
+ * before the first launch (two handles for one instant: an earlier version had a preparation
+ * launch between them; D = rowsum(dO o O) is now computed inside the dQ kernel), events[2] after
+ * the dQ kernel, events[3] after the dK/dV kernel.  The events stay owned by the caller.
  */
 int attn_bwd_timed(const attn_params* p, const uint8_t* block_mask, int32_t mask_block,
                    int64_t mask_stride_h, const void* Q, const void* K, const void* V,

@@ -6,13 +6,14 @@
 // (Eq. (4), Appendix B.2), and
 //     dV = P_dropped^T dO,  dP = (dO V^T) o Z,  dS = P o (dP - D),  dQ = tau dS K,  dK = tau dS^T Q.
 // The schedule differs from the paper's single K/V-outer loop with dQ read-modify-written in
-// HBM: three launches, none of which writes a partial result to HBM.
-//   1. rowdot_kernel : D = rowsum(dO o O), L in base 2                  (HBM-bound, tiny)
-//   2. dq_kernel     : a workgroup owns 128 query rows and sweeps K/V tiles; dQ stays in
-//                      registers (S^T, dP^T layout: lane = query, like the forward kernel)
-//   3. dkv_rs_kernel (attn_bwd_dkv.hip): a workgroup owns 128 keys and sweeps Q/dO tiles;
-//                      dK, dV stay in registers (S, dP layout: lane = key)
-// S and dP are therefore recomputed in both 2 and 3 (seven tile products per (i, j) instead of
+// HBM: two launches, neither of which writes a partial result to HBM.
+//   1. dq_kernel     : a workgroup owns 128 query rows and sweeps K/V tiles; dQ stays in
+//                      registers (S^T, dP^T layout: lane = query, like the forward kernel).  It
+//                      also computes D = rowsum(dO o O) of its rows and leaves -D and L in base 2
+//                      in the scratch vectors for the second launch.
+//   2. dK/dV kernel (attn_bwd_dkv.hip, attn_bwd_dkv_fr.hip): a workgroup owns 128 keys and
+//                      sweeps Q/dO tiles; dK, dV stay in registers (S, dP layout: lane = key)
+// S and dP are therefore recomputed in both launches (seven tile products per (i, j) instead of
 // five) in exchange for no atomics, no fp32 dQ round trip and bit-reproducible gradients.
 #include "attn_common.h"
 #include "attn_tiles.h"
@@ -24,45 +25,6 @@ namespace {
 
 constexpr int NT = 256;
 constexpr int TILE = 64;  // keys of the streamed tile
-
-// ---------------------------------------------------------------------------------------------
-// -D_i = -sum_d dO[i][d] * O[i][d] (stored negated: the tile kernels start the dP accumulators
-// from it, so that dP - D needs no instruction of its own); also the row statistic in the form the tile kernels use it:
-// L_i * log2(e), and +inf for a fully masked row (L_i = -inf) so that exp2(s - L) is 0 there.
-template <typename T, int D>
-__global__ __launch_bounds__(256) void rowdot_kernel(const KArgs a) {
-  typedef typename Vec<T>::x8 T8;
-  constexpr int CPR = D / 8;  // lanes per row
-  const int64_t rows = (int64_t)a.B * a.H * a.Nr;   // Nr = N rounded up to 128: the scratch vectors are padded per head
-  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (gid == 0 && a.seglist != nullptr) { a.seglist[0] = 0; a.seglist[1] = 0; }   // block-sparse: empty segment list, no blocks counted
-  const int64_t row = gid / CPR;
-  const int ch = (int)(gid % CPR);
-  const int64_t bh = row / a.Nr, i = row % a.Nr;
-  const bool real = row < rows && i < a.N;   // padding rows: D = 0, statistic = +inf (P = 0 there)
-  float acc = 0.f;
-  if (real) {
-    const int64_t off = (bh / a.H) * a.sb + (bh % a.H) * a.sh + i * a.sn + 8 * ch;
-    const T8 g = *(const T8*)((const T*)a.dO + off);
-    if (a.o_fp32) {
-      const f32x4 o0 = *(const f32x4*)((const float*)a.O + off);
-      const f32x4 o1 = *(const f32x4*)((const float*)a.O + off + 4);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) acc += (float)g[e] * o0[e] + (float)g[4 + e] * o1[e];
-    } else {
-      const T8 o = *(const T8*)((const T*)a.O + off);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) acc += (float)g[e] * (float)o[e];
-    }
-  }
-#pragma unroll
-  for (int s = CPR / 2; s >= 1; s >>= 1) acc += __shfl_xor(acc, s);
-  if (row < rows && ch == 0) {
-    a.Dvec[row] = -acc;
-    const float lse = real ? a.LSE[bh * a.N + i] : -INFINITY;
-    a.L2vec[row] = (lse == -INFINITY) ? INFINITY : lse * 1.4426950408889634f;
-  }
-}
 
 // ---------------------------------------------------------------------------------------------
 // dQ: workgroup = 128 query rows (4 wavefronts x 32), sweep over 64-key tiles.
@@ -114,16 +76,40 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const KArgs a) {
   const int qi = min(q0 + r, a.N - 1);
 
   T8 qf[KK], gf[KK];  // Q^T and dO^T fragments (B operands) of this lane's query
+  // -D_i = -sum_d dO[i][d] O[i][d] (Eq. (4), Appendix B.2), from the same 8-element pieces of the row
+  // that the dO fragments hold: this lane's half of the sum, completed with the partner lane below
+  float d_part = 0.f;
 #pragma unroll
   for (int kk = 0; kk < KK; ++kk) {
     const int64_t off = head_off + (int64_t)qi * a.sn + 16 * kk + 8 * g;
     qf[kk] = *(const T8*)((const T*)a.Q + off);
     gf[kk] = *(const T8*)((const T*)a.dO + off);
+    if (a.o_fp32) {
+      const f32x4 o0 = *(const f32x4*)((const float*)a.O + off);
+      const f32x4 o1 = *(const f32x4*)((const float*)a.O + off + 4);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) d_part += (float)gf[kk][e] * o0[e] + (float)gf[kk][4 + e] * o1[e];
+    } else {
+      const T8 o = *(const T8*)((const T*)a.O + off);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) d_part += (float)gf[kk][e] * (float)o[e];
+    }
   }
   const float lse = a.LSE[(int64_t)bh * a.N + qi];
-  // base-2 statistic; a row that saw no key has P = 0 everywhere
+  // base-2 statistic; a row that saw no key (or lies beyond a ragged end) has P = 0 everywhere
   const float l2 = (lse == -INFINITY || !row_ok) ? INFINITY : lse * 1.4426950408889634f;
-  const float neg_d = a.Dvec[(int64_t)bh * a.Nr + qi];   // -D_i
+  const float neg_d = row_ok ? -(d_part + xchg32(d_part)) : 0.f;   // -D_i
+  // The dK/dV kernel reads both per 64-row tile from the scratch vectors (padded to whole blocks
+  // of 128 rows per head: this workgroup writes all 128 of its block).  The tile kernels start
+  // their dP accumulators from -D, so that dP - D needs no instruction of its own.
+  if (g == 0) {
+    a.Dvec[(int64_t)bh * a.Nr + q0 + r] = neg_d;
+    a.L2vec[(int64_t)bh * a.Nr + q0 + r] = l2;
+  }
+  if (blockIdx.x == 0 && threadIdx.x == 0 && pass == 0 && a.seglist != nullptr) {
+    a.seglist[0] = 0;   // block-sparse: empty segment list, no blocks counted (the dK/dV planning
+    a.seglist[1] = 0;   // kernels run after this one)
+  }
 
   f32x16 dq[DB];
 #pragma unroll
@@ -265,13 +251,9 @@ template <> constexpr int kDtype<__bf16> = 1;
 
 template <typename T, int D>
 int launch_bwd_td(const KArgs& a, bool causal, bool dropout, bool sparse, hipStream_t s, hipEvent_t* ev) {
-  const int64_t rows = (int64_t)a.B * a.H * a.Nr;
-  const int64_t threads = rows * (D / 8);
   if (ev) (void)hipEventRecord(ev[0], s);
-  hipLaunchKernelGGL((rowdot_kernel<T, D>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, a);
-  int e = (int)hipGetLastError();
-  if (e != 0) return e;
-  if (ev) (void)hipEventRecord(ev[1], s);
+  int e = 0;
+  if (ev) (void)hipEventRecord(ev[1], s);   // (there is no separate preparation launch any more)
   const dim3 block(NT);
   // dense causal d = 64 dQ items are pairs of row blocks
   KArgs aq = a;
