@@ -239,7 +239,7 @@ def attn_bwd_timed(Q, K, V, O, dO, LSE, events, *, softmax_scale, block_mask=Non
                    causal=False, dropout_p=0.0, seed=0, offset=0, o_fp32=False, workspace=None,
                    grads=None, stream=None, key_lengths=None):
     """attn_bwd / attn_blocksparse_bwd that also records four caller-owned hipEvent_t handles
-    (ints) on the stream: before, after row-dot, after dQ, after dK/dV."""
+    (ints) on the stream: two before the first launch, one after dQ, one after dK/dV."""
     _same_layout(Q, K, V, dO)
     p = make_params(Q, softmax_scale, causal, dropout_p, seed, offset, o_fp32, stream, key_lengths)
     msh = 0 if block_mask is None else _mask_args(block_mask, Q.shape[1])

@@ -56,7 +56,7 @@ enum { kHeavyBlocks = 24, kSegBlocks = 12, kMaxSegs = 32, kSegHeader = 8, kCompu
 
 // Launchers (defined in the .hip files).  dtype: 0 fp16, 1 bf16.  Return hipError_t as int.
 int launch_fwd(const KArgs& a, int dtype, int d, bool causal, bool dropout, bool sparse, hipStream_t s);
-// ev: nullptr, or four events recorded before / between / after the three launches.
+// ev: nullptr, or four events: two recorded before the first launch, one after the dQ kernel, one after dK/dV.
 int launch_bwd(const KArgs& a, int dtype, int d, bool causal, bool dropout, bool sparse, hipStream_t s,
                hipEvent_t* ev);
 int launch_dropout_mask(const KArgs& a, uint8_t* keep, hipStream_t s);
