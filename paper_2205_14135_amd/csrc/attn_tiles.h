@@ -19,60 +19,14 @@ __device__ __forceinline__ int lane_id_here() {
 // Asynchronous copy of a [64][D] tile from global memory straight into swizzled LDS (no register
 // staging, no LDS store instructions): each global_load_lds_dwordx4 moves 64 lanes x 16 bytes to
 // 1 KB of consecutive LDS, so lane l of copy q lands on row q*(64/CPR) + l/CPR, physical chunk
-// l%CPR, and therefore fetches the logical chunk (l%CPR) ^ swizzle(row) of that row.  NW
-// wavefronts (numbered 0..NW-1 by the caller) issue (D/8)/NW copies each.  Completion is counted
-// by vmcnt: the compiler waits for it before the next workgroup barrier.
-template <typename T, int D, int NW> struct TileDma {
-  static constexpr int CPR = D / 8, RPC = 64 / CPR, NCOPY = D / 8, PER_WAVE = NCOPY / NW;
-  static_assert(NCOPY % NW == 0, "copies must divide evenly over the wavefronts");
-  int64_t goff[PER_WAVE];   // element offset of this lane's chunk inside a tile whose row 0 is at 0
-  int wave;
-  __device__ __forceinline__ void init(int64_t sn, int wave_index) {
-    const int lane = threadIdx.x & 63;
-    wave = wave_index;
-#pragma unroll
-    for (int p = 0; p < PER_WAVE; ++p) {
-      const int row = (wave * PER_WAVE + p) * RPC + lane / CPR;
-      goff[p] = (int64_t)row * sn + 8 * ((lane % CPR) ^ swz_bits<D>(row));
-    }
-  }
-  __device__ __forceinline__ void copy(const T* g_row0, T* lds_tile) const {
-#if defined(__HIP_DEVICE_COMPILE__)   // the builtin exists in the device pass only
-#pragma unroll
-    for (int p = 0; p < PER_WAVE; ++p)
-      __builtin_amdgcn_global_load_lds(g_row0 + goff[p], lds_tile + (wave * PER_WAVE + p) * 512, 16, 0, 0);
-#else
-    (void)g_row0; (void)lds_tile;
-#endif
-  }
-  // The last tile of a tensor whose row count is not a multiple of 64: only rows_valid (>= 1) rows
-  // exist; the LDS rows beyond them receive a copy of the last valid row (finite values that the
-  // kernels mask), so that nothing outside the tensor is read.
-  __device__ __forceinline__ void copy_tail(const T* g_row0, T* lds_tile, int64_t sn, int rows_valid) const {
-#if defined(__HIP_DEVICE_COMPILE__)
-    const int lane_row = lane_id_here() / CPR;
-#pragma unroll
-    for (int p = 0; p < PER_WAVE; ++p) {
-      const int excess = max((wave * PER_WAVE + p) * RPC + lane_row - (rows_valid - 1), 0);   // rows past the last one
-      __builtin_amdgcn_global_load_lds(g_row0 + (goff[p] - excess * sn), lds_tile + (wave * PER_WAVE + p) * 512, 16, 0, 0);
-    }
-#else
-    (void)g_row0; (void)lds_tile; (void)sn; (void)rows_valid;
-#endif
-  }
-  // tile whose first row is row0 of a tensor with n_rows rows (row0 < n_rows)
-  __device__ __forceinline__ void copy_rows(const T* g, int64_t sn, int row0, int n_rows, T* lds_tile) const {
-    if (row0 + 64 <= n_rows) copy(g + (int64_t)row0 * sn, lds_tile);
-    else copy_tail(g + (int64_t)row0 * sn, lds_tile, sn, n_rows - row0);
-  }
-};
-
-// The same copy, issued as a raw instruction that the compiler does not track.  With the builtin
-// the compiler makes every later LDS read that might alias the destination wait for the copy, and
-// with run-time buffer indices every read might; a copy issued this way stays in flight until
-// the caller waits for it with wait_async_copies() (which it must do, followed by a workgroup
-// barrier, before any wavefront reads the tile).  lds_byte_addr must be wavefront-uniform.
-// M0 carries the LDS base of the copy and is used by nothing else in these kernels.
+// l%CPR, and therefore fetches the logical chunk (l%CPR) ^ swizzle(row) of that row (TileAsync
+// below).  The copy is issued as a raw instruction that the compiler does not track: with the
+// builtin form of it the compiler makes every later LDS read that might alias the destination
+// wait for the copy, and with run-time buffer indices every read might; a copy issued this way
+// stays in flight until the caller waits for it with wait_async_copies() (which it must do,
+// followed by a workgroup barrier, before any wavefront reads the tile).  lds_byte_addr must be
+// wavefront-uniform.  M0 carries the LDS base of the copy and is used by nothing else in these
+// kernels.
 __device__ __forceinline__ void async_copy_b128(const void* gptr_lane, uint32_t lds_byte_addr) {
 #if defined(__HIP_DEVICE_COMPILE__)
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
@@ -126,7 +80,7 @@ __device__ __forceinline__ uint32_t lds_addr(const void* p) {
   return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)p;
 }
 
-// TileDma with untracked copies (see async_copy_b128).
+// The tile copy: NW wavefronts (numbered 0..NW-1 by the caller) issue (D/8)/NW copy instructions each.
 template <typename T, int D, int NW> struct TileAsync {
   static constexpr int CPR = D / 8, RPC = 64 / CPR, NCOPY = D / 8, PER_WAVE = NCOPY / NW;
   static_assert(NCOPY % NW == 0, "copies must divide evenly over the wavefronts");
