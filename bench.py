@@ -170,7 +170,10 @@ def run_gpu(cfg, steps, warmup, seed, mask_override=None, nsets=1):
     if cfg["sparse"]:
         use_pp = False
     else:
-        use_pp = d == 128 and (cfg["p"] > 0 or N >= 1024 or (cfg["causal"] and N >= 512))
+        n_qt = (N + 255) // 256
+        pp_items = B * H * ((n_qt + 1) // 2 if cfg["causal"] else n_qt)
+        use_pp = (d == 128 and pp_items >= 256 and
+                  (cfg["causal"] if cfg["p"] > 0 else (N >= 1024 or (cfg["causal"] and N >= 512))))
     # dK/dV: the one-wavefront kernel at d <= 64, the role-split one at d = 128 (launch_dkv_rs())
     names = ["fwd_pp_kernel" if use_pp else "fwd_kernel", "dq_kernel",
              "dkv_fr_kernel" if d <= 64 else "dkv_rs_kernel"]

@@ -443,11 +443,8 @@ __global__ __launch_bounds__(256) void sparse_finish_kernel(const KArgs a) {
 
 // ATTN_DKV_VARIANT=rs keeps the role-split kernel at every head dimension (bench-time comparison)
 bool force_role_split() {
-  static const bool forced = [] {
-    const char* v = getenv("ATTN_DKV_VARIANT");
-    return v != nullptr && v[0] == 'r';
-  }();
-  return forced;
+  const char* v = getenv("ATTN_DKV_VARIANT");   // read on every call: tests switch it in-process
+  return v != nullptr && v[0] == 'r';
 }
 
 template <typename T, int D>

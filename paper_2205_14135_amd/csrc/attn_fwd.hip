@@ -337,18 +337,23 @@ __global__ void dropout_mask_kernel(const KArgs a, uint8_t* keep) {
 }  // namespace
 
 int launch_fwd(const KArgs& a, int dtype, int d, bool causal, bool dropout, bool sparse, hipStream_t s) {
-  // Dense d = 128 problems take the two-group ping-pong kernel (attn_fwd_pp.hip) from N = 1024 on
-  // (from 512 under the causal mask, where its paired work items balance better, and always with
-  // dropout): there the matrix blocks are long enough for the MFMA / softmax overlap to pay
-  // (measured: 4-6 % faster than this file's kernel from N = 2048, equal at 1024, 6 % slower at
-  // 512 without a mask).  At d = 64 the vector ALU work dominates and two free-running workgroups
-  // per compute unit (this file) measured faster at every N; block-sparse problems always take
-  // this kernel.  ATTN_FWD_VARIANT=base|pp overrides the choice (bench-time comparison).
-  static const char variant = [] {
-    const char* v = getenv("ATTN_FWD_VARIANT");
-    return v != nullptr ? v[0] : 'a';
-  }();
-  bool use_pp = d == 128 && (dropout || a.N >= 1024 || (causal && a.N >= 512));
+  // Which dense d = 128 problems take the two-group ping-pong kernel (attn_fwd_pp.hip), by
+  // measurement against this file's kernel (two free-running 4-wave workgroups per compute unit):
+  //   no dropout: from N = 1024 on (4-6 % faster from 2048, equal at 1024, 6 % slower at 512), under
+  //     the causal mask from N = 512 (its paired work items balance better);
+  //   dropout: only under the causal mask (the pairing again: 10-15 % faster); without a mask the
+  //     free-running kernel is ~3 % faster at every N (the generator is plain vector ALU work);
+  //   and only if its 256-row work items (pairs of them under the causal mask) are at least as
+  //     many as the compute units: a problem with few heads would leave half of the chip idle.
+  // At d <= 64 the vector ALU work dominates and this file's kernel measured faster at every N;
+  // block-sparse problems always take it.  ATTN_FWD_VARIANT=base|pp overrides the choice
+  // (bench-time comparison).
+  const char* forced = getenv("ATTN_FWD_VARIANT");   // read on every call: tests switch it in-process
+  const char variant = forced != nullptr ? forced[0] : 'a';
+  const int n_qt256 = (a.N + 255) / 256;
+  const int64_t pp_items = (int64_t)a.B * a.H * (causal ? (n_qt256 + 1) / 2 : n_qt256);
+  bool use_pp = d == 128 && pp_items >= kComputeUnits &&
+                (dropout ? causal : (a.N >= 1024 || (causal && a.N >= 512)));
   if (variant == 'b') use_pp = false;
   if (variant == 'p' && d != 32) use_pp = true;
   if (!sparse && use_pp) return launch_fwd_pp(a, dtype, d, causal, dropout, s);

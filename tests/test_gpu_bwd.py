@@ -11,6 +11,11 @@ from paper_2205_14135_amd import binding, inputs
 pytestmark = pytest.mark.gpu
 
 
+@pytest.fixture(autouse=True)
+def _both_kernels(dkv_variant):
+    """Every test of this module runs with the library's own kernel choice and with the other kernel forced."""
+
+
 def test_c1_tiny_dense():
     t, dev = hp.make_case(1, 1, 128, 64, "fp16", inputs.BASE_SEED + 0)
     res = hp.check_backward(t, dev, "fp16", 1 / math.sqrt(64))

@@ -8,6 +8,11 @@ import torch
 from tests import helpers as hp
 from paper_2205_14135_amd import binding, inputs
 
+
+@pytest.fixture(autouse=True)
+def _both_kernels(fwd_variant):
+    """Every test of this module runs with the library's own kernel choice and with the other kernel forced."""
+
 pytestmark = pytest.mark.gpu
 
 

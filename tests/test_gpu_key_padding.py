@@ -12,6 +12,13 @@ from paper_2205_14135_amd import binding, inputs
 pytestmark = pytest.mark.gpu
 
 
+@pytest.fixture(autouse=True)
+def _both_kernels(fwd_variant, dkv_variant):
+    """Every test of this module runs with the library's own choice of forward and of dK/dV kernel
+    and with the other kernel forced (four combinations)."""
+
+
+
 def _case(B, H, N, d, dtype, lengths, **kw):
     t, dev = hp.make_case(B, H, N, d, dtype, inputs.BASE_SEED + 700 + N + d)
     tau = 1 / math.sqrt(d)

@@ -16,6 +16,13 @@ from paper_2205_14135_amd import binding, inputs
 
 pytestmark = pytest.mark.gpu
 
+
+@pytest.fixture(autouse=True)
+def _both_kernels(fwd_variant, dkv_variant):
+    """Every test of this module runs with the library's own choice of forward and of dK/dV kernel
+    and with the other kernel forced (four combinations)."""
+
+
 GUARD_ROWS = 130
 SENTINEL = 512.0
 
@@ -95,7 +102,7 @@ def _run(B, H, N, d, dtype, *, causal=False, p=0.0, lengths=None, o_fp32=False, 
 @pytest.mark.parametrize("N", [1, 37, 64, 65, 100, 129, 200, 333])
 @pytest.mark.parametrize("causal", [False, True])
 def test_ragged_d64(N, causal):
-    """d = 64: free-running forward, paired causal items, dQ and role-split dK/dV kernels."""
+    """d = 64: free-running forward, paired causal items, dQ and both dK/dV kernels."""
     print(_run(2, 2, N, 64, "bf16", causal=causal))
 
 
