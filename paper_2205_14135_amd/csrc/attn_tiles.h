@@ -81,8 +81,9 @@ __device__ __forceinline__ uint32_t lds_addr(const void* p) {
 }
 
 // The tile copy: NW wavefronts (numbered 0..NW-1 by the caller) issue (D/8)/NW copy instructions each.
-template <typename T, int D, int NW> struct TileAsync {
-  static constexpr int CPR = D / 8, RPC = 64 / CPR, NCOPY = D / 8, PER_WAVE = NCOPY / NW;
+// ROWS: rows of the tile (64 unless a kernel streams smaller tiles).
+template <typename T, int D, int NW, int ROWS = 64> struct TileAsync {
+  static constexpr int CPR = D / 8, RPC = 64 / CPR, NCOPY = ROWS / RPC, PER_WAVE = NCOPY / NW;
   static_assert(NCOPY % NW == 0, "copies must divide evenly over the wavefronts");
   uint32_t goff[PER_WAVE];   // byte offset of this lane's chunk inside a tile whose row 0 is at 0
   int wave;                  // (the host checks that 64 rows of the tensor span less than 2^31 bytes)
@@ -116,7 +117,7 @@ template <typename T, int D, int NW> struct TileAsync {
   }
   // tile whose first row is row0 of a tensor with n_rows rows (row0 < n_rows)
   __device__ __forceinline__ void copy_rows(const T* g, int64_t sn, int row0, int n_rows, const T* lds_tile) const {
-    if (row0 + 64 <= n_rows) copy(g + (int64_t)row0 * sn, lds_tile);
+    if (row0 + ROWS <= n_rows) copy(g + (int64_t)row0 * sn, lds_tile);
     else copy_tail(g + (int64_t)row0 * sn, lds_tile, sn, n_rows - row0);
   }
 };
