@@ -174,9 +174,15 @@ def run_gpu(cfg, steps, warmup, seed, mask_override=None, nsets=1):
         pp_items = B * H * ((n_qt + 1) // 2 if cfg["causal"] else n_qt)
         use_pp = (d == 128 and pp_items >= 256 and
                   (cfg["causal"] if cfg["p"] > 0 else (N >= 1024 or (cfg["causal"] and N >= 512))))
-    # dK/dV: the one-wavefront kernel at d <= 64, the role-split one at d = 128 (launch_dkv_rs())
-    names = ["fwd_pp_kernel" if use_pp else "fwd_kernel", "dq_kernel",
-             "dkv_fr_kernel" if d <= 64 else "dkv_rs_kernel"]
+    # dK/dV: the one-wavefront kernels at d <= 64 and (no mask, no dropout) at d = 128, else the
+    # role-split one (launch_dkv_rs())
+    if d <= 64:
+        dkv = "dkv_fr_kernel"
+    elif not cfg["sparse"] and not cfg["causal"] and cfg["p"] == 0:
+        dkv = "dkv_fr128_kernel"
+    else:
+        dkv = "dkv_rs_kernel"
+    names = ["fwd_pp_kernel" if use_pp else "fwd_kernel", "dq_kernel", dkv]
     # events: e[0] before the forward, e[1] = e[2] before the backward, e[3] after dQ, e[4] after dK/dV
     spans = [(0, 1), (1, 3), (3, 4)]
     per_step = {n: [] for n in names}

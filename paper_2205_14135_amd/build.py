@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libattn_gfx950.so")
-SOURCES = ["attn_fwd.hip", "attn_fwd_pp.hip", "attn_bwd.hip", "attn_bwd_dkv.hip", "attn_bwd_dkv_fr.hip", "attn_probe.hip", "attn_api.cpp"]
+SOURCES = ["attn_fwd.hip", "attn_fwd_pp.hip", "attn_bwd.hip", "attn_bwd_dkv.hip", "attn_bwd_dkv_fr.hip", "attn_bwd_dkv_fr128.hip", "attn_probe.hip", "attn_api.cpp"]
 FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-x", "hip",
     # packed fp32 VALU forms are switched off on purpose (they have misbehaved on the test machines)

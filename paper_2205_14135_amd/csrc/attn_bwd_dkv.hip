@@ -501,6 +501,8 @@ int launch_dkv_rs(const KArgs& a, int dtype, int d, bool causal, bool dropout, b
   // (attn_bwd_dkv_fr.hip; the block-sparse ones from inside launch_td, between the column
   // planning and the finish kernel).
   if (!sparse && d <= 64 && !force_role_split()) return launch_dkv_fr(a, dtype, d, causal, dropout, false, 0, s);
+  // d = 128, no mask, no dropout: the one-wavefront kernel with the V block in LDS (attn_bwd_dkv_fr128.hip)
+  if (!sparse && d == 128 && !causal && !dropout && !force_role_split()) return launch_dkv_fr128(a, dtype, s);
   if (dtype == 0 && d == 32) return launch_td<_Float16, 32>(a, causal, dropout, sparse, s);
   if (dtype == 1 && d == 32) return launch_td<__bf16, 32>(a, causal, dropout, sparse, s);
   if (dtype == 0 && d == 64) return launch_td<_Float16, 64>(a, causal, dropout, sparse, s);
