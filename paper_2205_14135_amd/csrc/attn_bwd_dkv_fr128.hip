@@ -13,6 +13,8 @@
 // than the role-split kernel of attn_bwd_dkv.hip at N = 4096 and 10 % at N = 1024; the causal form
 // of this kernel does not fit the register file, and dropout is not implemented: those problems
 // keep the role-split kernel.
+#include <type_traits>
+
 #include "attn_common.h"
 #include "attn_tiles.h"
 
@@ -27,11 +29,15 @@ template <typename T>
 __global__ __launch_bounds__(NT, 2) void dkv_fr128_kernel(const KArgs a) {
   typedef typename Vec<T>::x8 T8;
   constexpr int KK = D / 16, DB = D / 32;
-  __shared__ __attribute__((aligned(16))) T Qs[2][QT * D];
-  __shared__ __attribute__((aligned(16))) T Gs[2][QT * D];       // dO tiles
-  __shared__ __attribute__((aligned(16))) T Vb[128 * D];         // V rows of this key block
-  __shared__ __attribute__((aligned(16))) float Ls[2][64];       // base-2 row statistic (first QT entries used:
-  __shared__ __attribute__((aligned(16))) float Ds[2][64];       // -D_i                  a copy moves 64 floats)
+  // One LDS block, so that every address is a per-lane register plus a 16-bit immediate: the row
+  // vectors first (1 KB), then the Q tiles, the dO tiles and the V rows of this key block.
+  constexpr int kVecBytes = 4 * 64 * 4;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[kVecBytes + (4 * QT * D + 128 * D) * sizeof(T)];
+  float* const Ls0 = (float*)smem;                 // base-2 row statistic: Ls0 + 64 buf (first QT entries used:
+  float* const Ds0 = Ls0 + 2 * 64;                 // -D_i:                 Ds0 + 64 buf  a copy moves 64 floats)
+  T* const Qs0 = (T*)(smem + kVecBytes);           // Q tiles:  Qs0 + buf QT D
+  T* const Gs0 = Qs0 + 2 * QT * D;                 // dO tiles: Gs0 + buf QT D
+  T* const Vb = Qs0 + 4 * QT * D;                  // V rows of this key block
 
   const int n_kt = a.T;   // ceil(N / 128): the last key block may be ragged
   const int item = xcd_item(a.n_items, a.chunk);
@@ -75,11 +81,11 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr128_kernel(const KArgs a) {
   TileAsync<T, D, 4, 64> dma64;    // the V block: two 64-row pieces
   dma64.init(a.sn, wave);
   auto fetch_tile = [&](int t, int buf) {
-    dma.copy_rows(Qg, a.sn, t * QT, a.N, Qs[buf]);
-    dma.copy_rows(Gg, a.sn, t * QT, a.N, Gs[buf]);
+    dma.copy_rows(Qg, a.sn, t * QT, a.N, Qs0 + buf * QT * D);
+    dma.copy_rows(Gg, a.sn, t * QT, a.N, Gs0 + buf * QT * D);
     const int row = min(t * QT + lane, a.Nr - 1);   // whole-wavefront copies: 64 floats, clamped to the head
-    if (wave == 1) async_copy_b32(Lg + row, __builtin_amdgcn_readfirstlane(lds_addr(Ls[buf])));
-    if (wave == 2) async_copy_b32(Dg + row, __builtin_amdgcn_readfirstlane(lds_addr(Ds[buf])));
+    if (wave == 1) async_copy_b32(Lg + row, __builtin_amdgcn_readfirstlane(lds_addr(Ls0 + 64 * buf)));
+    if (wave == 2) async_copy_b32(Dg + row, __builtin_amdgcn_readfirstlane(lds_addr(Ds0 + 64 * buf)));
   };
   const float c = a.scale_log2;
   constexpr int PF = 4;
@@ -88,15 +94,17 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr128_kernel(const KArgs a) {
   if (kt * 128 < a.N) dma64.copy_rows(Vg, a.sn, kt * 128, a.N, Vb);
   if (kt * 128 + 64 < a.N) dma64.copy_rows(Vg, a.sn, kt * 128 + 64, a.N, Vb + 64 * D);
   else if (kt * 128 < a.N) dma64.copy_rows(Vg, a.sn, kt * 128, a.N, Vb + 64 * D);   // all of these keys are masked
-  int buf = 0;
   if (first < limit) fetch_tile(first, 0);
   wait_async_copies();
   __syncthreads();
-  for (int t = first; t < limit; ++t) {
+  // One query tile.  The buffer index is a compile-time constant (the loop below is unrolled by
+  // two), so that every LDS address is a per-lane register plus an immediate offset.
+  auto tile_step = [&](int t, auto buf_c) {
+    constexpr int buf = decltype(buf_c)::value;
     if (t + 1 < limit) fetch_tile(t + 1, buf ^ 1);
     {
-      const T* Qt = Qs[buf];
-      const T* Gt = Gs[buf];
+      const T* Qt = Qs0 + buf * QT * D;
+      const T* Gt = Gs0 + buf * QT * D;
       // ---- S = Q K^T and dP = dO V^T (32 queries x 32 keys each) as one stream of alternating
       // MFMAs: consecutive instructions write different accumulators.  dP starts from -D; its
       // second operand (the V fragments) comes from LDS too.
@@ -111,7 +119,7 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr128_kernel(const KArgs a) {
         for (int f = 0; f < PF2; ++f) { rq[f] = qfrag(f); rg[f] = gfrag(f); rv[f] = vfrag(f); }
 #pragma unroll
         for (int i4 = 0; i4 < 4; ++i4) {
-          const f32x4 c4 = *(const f32x4*)(&Ds[buf][8 * i4 + 4 * g]);
+          const f32x4 c4 = *(const f32x4*)(Ds0 + 64 * buf + 8 * i4 + 4 * g);
 #pragma unroll
           for (int e = 0; e < 4; ++e) { dp[4 * i4 + e] = c4[e]; s[4 * i4 + e] = 0.f; }
         }
@@ -133,7 +141,7 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr128_kernel(const KArgs a) {
       T8 pf[2];
 #pragma unroll
       for (int i4 = 0; i4 < 4; ++i4) {
-        const f32x4 l4 = *(const f32x4*)(&Ls[buf][8 * i4 + 4 * g]);
+        const f32x4 l4 = *(const f32x4*)(Ls0 + 64 * buf + 8 * i4 + 4 * g);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int i = 4 * i4 + e;
@@ -174,7 +182,10 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr128_kernel(const KArgs a) {
     }
     wait_async_copies();
     __syncthreads();
-    buf ^= 1;
+  };
+  for (int t = first; t < limit; t += 2) {
+    tile_step(t, std::integral_constant<int, 0>());
+    if (t + 1 < limit) tile_step(t + 1, std::integral_constant<int, 1>());
   }
   {
     // 4 wavefronts x 32 rows x 128 = 32 KB per gradient: the V block, then the four tile buffers
