@@ -32,8 +32,23 @@ template <typename T, int D, bool CAUSAL, bool DROPOUT, bool SPARSE>
 __global__ __launch_bounds__(NT, 2) void dq_kernel(const KArgs a) {
   typedef typename Vec<T>::x8 T8;
   constexpr int KK = D / 16, DB = D / 32;
-  __shared__ __attribute__((aligned(16))) T Ks[2][TILE * D];   // double buffered, filled by async copies
-  __shared__ __attribute__((aligned(16))) T Vs[2][TILE * D];
+  // K and V tiles, double buffered, filled by async copies.  Without the causal mask they form one
+  // LDS block (K tile of buffer b at b TILE D, V tile at (2 + b) TILE D), so that an LDS address
+  // is a per-lane register plus an immediate offset once the buffer index is a compile-time
+  // constant (see tile_step below); the causal kernels, which cannot afford that unrolling, keep
+  // two arrays (the form that the register allocator handles without spilling).
+  T* Ks0;
+  T* Vs0;
+  if constexpr (!CAUSAL) {
+    __shared__ __attribute__((aligned(16))) T smem[4 * TILE * D];
+    Ks0 = smem;
+    Vs0 = smem + 2 * TILE * D;
+  } else {
+    __shared__ __attribute__((aligned(16))) T Ks[2 * TILE * D];
+    __shared__ __attribute__((aligned(16))) T Vs[2 * TILE * D];
+    Ks0 = Ks;
+    Vs0 = Vs;
+  }
 
   const int item = xcd_item(a.n_items, a.chunk);
   if (item < 0) return;
@@ -134,21 +149,27 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const KArgs a) {
 
   const float c = a.scale_log2;
   int jt = it.next();
-  int buf = 0;
   if (jt >= 0) {
-    dma.copy_rows(Kg, a.sn, jt * TILE, a.N, Ks[0]);
-    dma.copy_rows(Vg, a.sn, jt * TILE, a.N, Vs[0]);
+    dma.copy_rows(Kg, a.sn, jt * TILE, a.N, Ks0);
+    dma.copy_rows(Vg, a.sn, jt * TILE, a.N, Vs0);
   }
   wait_async_copies();
   __syncthreads();   // tile 0 has landed, and so have the Q / dO fragments
+  // Without the causal mask the tile loop is unrolled by two, so that the buffer index is a
+  // constant in each copy of its body; the causal kernels have no registers for two copies.
+  constexpr int UNROLL = CAUSAL ? 1 : 2;
+  int buf_rt = 0;
   while (jt >= 0) {
+#pragma unroll
+  for (int u = 0; u < UNROLL; ++u) {
+    const int buf = UNROLL == 2 ? u : buf_rt;
     const int jn = it.next();
     if (jn >= 0) {   // next tile streams into the other buffer while this one is used
-      dma.copy_rows(Kg, a.sn, jn * TILE, a.N, Ks[buf ^ 1]);
-      dma.copy_rows(Vg, a.sn, jn * TILE, a.N, Vs[buf ^ 1]);
+      dma.copy_rows(Kg, a.sn, jn * TILE, a.N, Ks0 + (buf ^ 1) * TILE * D);
+      dma.copy_rows(Vg, a.sn, jn * TILE, a.N, Vs0 + (buf ^ 1) * TILE * D);
     }
-    const T* Kt = Ks[buf];
-    const T* Vt = Vs[buf];
+    const T* Kt = Ks0 + buf * TILE * D;
+    const T* Vt = Vs0 + buf * TILE * D;
 
     const int k0 = jt * TILE;
     if (!CAUSAL || k0 <= q0 + 31) {
@@ -238,10 +259,12 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const KArgs a) {
     wait_async_copies();
     __syncthreads();   // next tile has landed, and everyone is done with this buffer
     jt = jn;
-    buf ^= 1;
+    buf_rt ^= 1;
+    if (jt < 0) break;
+  }
   }
   // the loop ends on a barrier (or never touched LDS): the tile buffers stage the output rows
-  T* stage = (wave < 2 ? &Ks[0][0] + wave * 32 * D : &Vs[0][0] + (wave - 2) * 32 * D);
+  T* stage = (wave < 2 ? Ks0 + wave * 32 * D : Vs0 + (wave - 2) * 32 * D);
   store_rows_coalesced<T, D>(stage, (T*)a.dQ + head_off + (int64_t)q0 * a.sn, a.sn, dq, a.tau, a.N - q0);
   }  // for pass
 }
