@@ -152,8 +152,9 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
   // for LDS latency on every instruction.
   constexpr int PF = 4;
   // product of a row-read tile with the register fragments: sd[qb] = Tile[32 qb .. +31][:] . kvf
-  // cinit: 64 per-row start values of the accumulator (nullptr: zero)
-  auto row_product = [&](const T* tile, const float* cinit) {
+  // The accumulators start from zero or (with_init: a literal at every call, a test of the pointer
+  // would be evaluated at run time) from the 64 per-row values at cinit
+  auto row_product = [&](const T* tile, const bool with_init, const float* cinit) {
     auto frag = [&](int f) { return *(const T8*)(tile + lds_off<D>(32 * (f & 1) + r, 2 * (f >> 1) + g)); };  // f = 2 kk + qb
     T8 ring[PF];
 #pragma unroll
@@ -164,7 +165,7 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
       const T8 cur = ring[f % PF];
       if (f < 2) {
         f32x16 z;
-        if (cinit != nullptr) {
+        if (with_init) {
 #pragma unroll
           for (int i4 = 0; i4 < 4; ++i4) {
             const f32x4 c4 = *(const f32x4*)(cinit + 32 * f + 8 * i4 + 4 * g);
@@ -241,7 +242,7 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
 
   // ---- role A, tile with first query i0, buffers (q3, p2)
   auto role_a = [&](int i0, int q4, int g3, int p2) {
-    row_product(Qs[q4], nullptr);                          // S = Q K^T
+    row_product(Qs[q4], false, nullptr);                         // S = Q K^T
     uint32_t kw[2][4] = {{0, 0, 0, 0}, {0, 0, 0, 0}};
     if constexpr (DROPOUT) {
       const uint32_t mine = draw_keep(i0);
@@ -337,7 +338,7 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
     } else {
       if (have_prev && prev_active) role_b_ds_dk((q4 + 3) & 3, p2 ^ 1);
       // dP = dO V^T; without dropout it starts from -D, so the result is dP - D
-      if (active) row_product(Gs[g3], DROPOUT ? nullptr : Ds[q4]);
+      if (active) row_product(Gs[g3], !DROPOUT, Ds[q4]);
     }
     have_prev = true;
     prev_active = active;

@@ -128,8 +128,10 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr_kernel(const KArgs a) {
 
   // LDS operand reads run PF fragments ahead of the MFMA that consumes them
   constexpr int PF = 4;
-  // out[qb] = Tile[32 qb .. +31][:] . frags  (cinit: 64 per-row start values, nullptr = zero)
-  auto row_product = [&](const T* tile, const T8 (&bfrag)[KK], const float* cinit, f32x16 (&out)[2]) {
+  // out[qb] = Tile[32 qb .. +31][:] . frags, starting from zero or (with_init: a literal at every
+  // call, a test of the pointer would be evaluated at run time) from the 64 per-row values at cinit
+  auto row_product = [&](const T* tile, const T8 (&bfrag)[KK], const bool with_init, const float* cinit,
+                         f32x16 (&out)[2]) {
     auto frag = [&](int f) { return *(const T8*)(tile + lds_off<D>(32 * (f & 1) + r, 2 * (f >> 1) + g)); };  // f = 2 kk + qb
     T8 ring[PF];
 #pragma unroll
@@ -140,7 +142,7 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr_kernel(const KArgs a) {
       const T8 cur = ring[f % PF];
       if (f < 2) {
         f32x16 z;
-        if (cinit != nullptr) {
+        if (with_init) {
 #pragma unroll
           for (int i4 = 0; i4 < 4; ++i4) {
             const f32x4 c4 = *(const f32x4*)(cinit + 32 * f + 8 * i4 + 4 * g);
@@ -223,7 +225,7 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr_kernel(const KArgs a) {
     const int i0 = t * TILE;
     if (!CAUSAL || i0 + TILE - 1 >= kw0) {
       f32x16 s[2], dp[2];
-      row_product(Qs[buf], kf, nullptr, s);                 // S = Q K^T
+      row_product(Qs[buf], kf, false, nullptr, s);                // S = Q K^T
       uint32_t kw[2][4] = {{0, 0, 0, 0}, {0, 0, 0, 0}};
       if constexpr (DROPOUT) keep_words(draw_keep(i0), kw);
       if (kw0 + 32 > len) {   // this wavefront holds padded keys: their logits become -inf, hence P = 0
@@ -257,7 +259,7 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr_kernel(const KArgs a) {
         }
       col_product(Gs[buf], pf, dv);                          // dV^T += dO^T P_dropped
       // dP = dO V^T; without dropout it starts from -D, so the result is dP - D
-      row_product(Gs[buf], vf, DROPOUT ? nullptr : Ds[buf], dp);
+      row_product(Gs[buf], vf, !DROPOUT, Ds[buf], dp);
       T8 dsf[4];
 #pragma unroll
       for (int qb = 0; qb < 2; ++qb)
