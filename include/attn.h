@@ -33,7 +33,7 @@
  *     Functions return ATTN_OK (0) or a negative attn_status; they never
  *     abort, throw, or print.
  *
- * Supported in this version: d in {32, 64, 128}; any N >= 1 for the dense entry
+ * Supported in this version: d in {16, 32, 64, 128}; any N >= 1 for the dense entry
  * points (a last block of fewer than 128 tokens is handled inside the kernels:
  * nothing outside the [B,H,N,d] tensors is read or written), N a multiple of
  * 128 for the block-sparse ones; tau finite and > 0; 0 <= p_drop < 1;
@@ -54,7 +54,7 @@ typedef enum {
   ATTN_ERR_NULL = -1,       /* a required pointer is NULL */
   ATTN_ERR_SHAPE = -2,      /* B, H, N out of range, bad strides, block-sparse with N % 128 != 0 */
   ATTN_ERR_DTYPE = -3,      /* dtype is neither ATTN_FP16 nor ATTN_BF16 */
-  ATTN_ERR_HEADDIM = -4,    /* d not in {32, 64, 128} */
+  ATTN_ERR_HEADDIM = -4,    /* d not in {16, 32, 64, 128} */
   ATTN_ERR_DROPOUT_P = -5,  /* p_drop not in [0, 1) or NaN */
   ATTN_ERR_SCALE = -6,      /* softmax_scale not finite or <= 0 */
   ATTN_ERR_WORKSPACE = -7,  /* workspace NULL, misaligned (256 B) or too small */

@@ -50,7 +50,7 @@ def flash_attention(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, *, softma
     """softmax(scale * q k^T + mask) v with dropout on the probabilities; exact attention.
 
     q, k, v: [B,H,N,d] fp16 or bf16 CUDA tensors with identical shape and strides, d contiguous,
-    d in {32, 64, 128}.  softmax_scale defaults to 1/sqrt(d).  key_lengths: int32 [B] true lengths
+    d in {16, 32, 64, 128}.  softmax_scale defaults to 1/sqrt(d).  key_lengths: int32 [B] true lengths
     (key-padding mask).  block_mask: uint8 [T,T] or [H,T,T] over 128 x 128 blocks (then N % 128 == 0).
     With dropout_p > 0 the mask is a pure function of (seed, offset, b, h, i, j); seed defaults to a
     draw from torch's CPU generator, so torch.manual_seed makes a run reproducible.

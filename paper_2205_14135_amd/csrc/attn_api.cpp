@@ -24,7 +24,7 @@ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 int check_params(const attn_params* p, Checked* out) {
   if (p == nullptr) return ATTN_ERR_NULL;
   if (p->dtype != ATTN_FP16 && p->dtype != ATTN_BF16) return ATTN_ERR_DTYPE;
-  if (p->d != 32 && p->d != 64 && p->d != 128) return ATTN_ERR_HEADDIM;
+  if (p->d != 16 && p->d != 32 && p->d != 64 && p->d != 128) return ATTN_ERR_HEADDIM;
   if (p->B <= 0 || p->H <= 0 || p->N <= 0) return ATTN_ERR_SHAPE;
   if (p->N > (1 << 30)) return ATTN_ERR_SHAPE;
   const int T = (p->N + attn::kMaskBlock - 1) / attn::kMaskBlock;   // a ragged last block is allowed (dense entry points)
@@ -46,6 +46,7 @@ int check_params(const attn_params* p, Checked* out) {
   std::memset(&k, 0, sizeof(k));
   k.sb = sb; k.sh = sh; k.sn = sn;
   k.B = p->B; k.H = p->H; k.N = p->N; k.T = T; k.Nr = T * attn::kMaskBlock;
+  k.dvalid = p->d;
   k.tau = p->softmax_scale;
   k.scale_log2 = (float)((double)p->softmax_scale * 1.4426950408889634);
   k.keep_scale = 1.0f / (1.0f - p->dropout_p);
@@ -56,7 +57,7 @@ int check_params(const attn_params* p, Checked* out) {
   k.o_fp32 = p->o_fp32 != 0;
   k.klen = p->key_lengths;
   out->dtype = p->dtype;
-  out->d = p->d;
+  out->d = p->d == 16 ? 32 : p->d;   // head dimension 16 runs on the d = 32 kernels (zero upper half on chip)
   out->causal = p->causal != 0;
   out->dropout = p->dropout_p > 0.0f;
   out->stream = (hipStream_t)p->stream;
@@ -87,7 +88,8 @@ WsLayout ws_layout(const attn_params* p) {
   w.d_bytes = align_up(2 * (size_t)p->B * p->H * T * attn::kMaskBlock * sizeof(float), 256);
   // column counts, then the segment list: one counter plus at most kMaxSegs entries per column
   w.cnt_bytes = align_up(((size_t)p->B * p->H * T * (1 + attn::kMaxSegs) + 64) * sizeof(int), 256);
-  w.acc_bytes = align_up((size_t)p->B * p->H * p->N * p->d * sizeof(float), 256);
+  const size_t d_kernel = p->d == 16 ? 32 : p->d;   // the fp32 accumulators have the kernels' row length
+  w.acc_bytes = align_up((size_t)p->B * p->H * p->N * d_kernel * sizeof(float), 256);
   return w;
 }
 

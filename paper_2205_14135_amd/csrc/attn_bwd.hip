@@ -97,6 +97,11 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const KArgs a) {
 #pragma unroll
   for (int kk = 0; kk < KK; ++kk) {
     const int64_t off = head_off + (int64_t)qi * a.sn + 16 * kk + 8 * g;
+    if (D == 32 && 16 * kk + 8 * g >= a.dvalid) {   // head dimension 16: the upper columns are zeros
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { qf[kk][e] = (T)0.f; gf[kk][e] = (T)0.f; }
+      continue;
+    }
     qf[kk] = *(const T8*)((const T*)a.Q + off);
     gf[kk] = *(const T8*)((const T*)a.dO + off);
     if (a.o_fp32) {
@@ -145,7 +150,12 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const KArgs a) {
   TrOffsets<D> tro;
   tro.init();
   TileAsync<T, D, NT / 64> dma;
-  dma.init(a.sn, threadIdx.x >> 6);
+  dma.init(a.sn, threadIdx.x >> 6, D == 32 ? a.dvalid : D);
+  if (D == 32 && a.dvalid < D) {   // the copies leave columns >= 16 of the tile buffers untouched
+    zero_tiles(Ks0, 2 * TILE * D);
+    zero_tiles(Vs0, 2 * TILE * D);
+    __syncthreads();
+  }
 
   const float c = a.scale_log2;
   int jt = it.next();
@@ -265,7 +275,8 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const KArgs a) {
   }
   // the loop ends on a barrier (or never touched LDS): the tile buffers stage the output rows
   T* stage = (wave < 2 ? Ks0 + wave * 32 * D : Vs0 + (wave - 2) * 32 * D);
-  store_rows_coalesced<T, D>(stage, (T*)a.dQ + head_off + (int64_t)q0 * a.sn, a.sn, dq, a.tau, a.N - q0);
+  store_rows_coalesced<T, D>(stage, (T*)a.dQ + head_off + (int64_t)q0 * a.sn, a.sn, dq, a.tau, a.N - q0,
+                             D == 32 ? a.dvalid : D);
   }  // for pass
 }
 

@@ -437,6 +437,7 @@ __global__ __launch_bounds__(256) void sparse_finish_kernel(const KArgs a) {
 #pragma unroll
     for (int e = 0; e < 4; ++e) { ko[e] = (T)k4[e]; vo[e] = (T)v4[e]; }
     const int64_t o = head_off + (int64_t)(kt * 128 + row) * a.sn + colx;
+    if (D == 32 && colx >= a.dvalid) continue;   // head dimension 16: the tensors' rows end there
     *(T4*)((T*)a.dK + o) = ko;
     *(T4*)((T*)a.dV + o) = vo;
   }
@@ -463,7 +464,7 @@ int launch_td(KArgs a, bool causal, bool dropout, bool sparse, hipStream_t s) {
     a.n_items = a.B * a.H * ((a.T + 1) / 2);
     a.chunk = (a.n_items + kXcds - 1) / kXcds;
   }
-  if (sparse && D <= 64 && !force_role_split()) {
+  if (sparse && D <= 64 && (!force_role_split() || a.dvalid < D)) {
     // d <= 64: the kernel in which one wavefront does all four products, same work assignment
     int e = launch_dkv_fr(a, std::is_same<T, __bf16>::value ? 1 : 0, D, causal, dropout, true, kListGroups, s);
     if (e == 0) {
@@ -501,7 +502,8 @@ int launch_dkv_rs(const KArgs& a, int dtype, int d, bool causal, bool dropout, b
   // Problems with d <= 64 take the kernel in which one wavefront does all four products
   // (attn_bwd_dkv_fr.hip; the block-sparse ones from inside launch_td, between the column
   // planning and the finish kernel).
-  if (!sparse && d <= 64 && !force_role_split()) return launch_dkv_fr(a, dtype, d, causal, dropout, false, 0, s);
+  // (head dimension 16 exists in that kernel only)
+  if (!sparse && d <= 64 && (!force_role_split() || a.dvalid < d)) return launch_dkv_fr(a, dtype, d, causal, dropout, false, 0, s);
   // d = 128, no mask, no dropout: the one-wavefront kernel with the V block in LDS (attn_bwd_dkv_fr128.hip)
   if (!sparse && d == 128 && !causal && !dropout && !force_role_split()) return launch_dkv_fr128(a, dtype, s);
   if (dtype == 0 && d == 32) return launch_td<_Float16, 32>(a, causal, dropout, sparse, s);

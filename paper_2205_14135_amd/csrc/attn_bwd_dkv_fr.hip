@@ -91,6 +91,11 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr_kernel(const KArgs a) {
     const int64_t row_off = head_off + (int64_t)min(kj, a.N - 1) * a.sn;
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
+      if (D == 32 && 16 * kk + 8 * g >= a.dvalid) {   // head dimension 16: the upper columns are zeros
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { kf[kk][e] = (T)0.f; vf[kk][e] = (T)0.f; }
+        continue;
+      }
       kf[kk] = *(const T8*)((const T*)a.K + row_off + 16 * kk + 8 * g);
       vf[kk] = *(const T8*)((const T*)a.V + row_off + 16 * kk + 8 * g);
     }
@@ -117,7 +122,12 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr_kernel(const KArgs a) {
   TrOffsets<D> tro;
   tro.init();
   TileAsync<T, D, 4> dma;
-  dma.init(a.sn, wave);
+  dma.init(a.sn, wave, D == 32 ? a.dvalid : D);
+  if (D == 32 && a.dvalid < D) {   // the copies leave columns >= 16 of the tile buffers untouched
+    zero_tiles(&Qs[0][0], 2 * TILE * D);   // (again in every round: the buffers staged output rows)
+    zero_tiles(&Gs[0][0], 2 * TILE * D);
+    __syncthreads();
+  }
   auto fetch_tile = [&](int t, int buf) {
     dma.copy_rows(Qg, a.sn, t * TILE, a.N, Qs[buf]);
     dma.copy_rows(Gg, a.sn, t * TILE, a.N, Gs[buf]);
@@ -305,8 +315,9 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr_kernel(const KArgs a) {
     T* stage_v = &Qs[0][0] + wave * 32 * D;   // 4 wavefronts x 32 rows = the two Q buffers
     T* stage_k = &Gs[0][0] + wave * 32 * D;
     store_rows_coalesced<T, D>(stage_v, (T*)a.dV + head_off + (int64_t)kw0 * a.sn, a.sn, dv,
-                               DROPOUT ? a.keep_scale : 1.f, a.N - kw0);
-    store_rows_coalesced<T, D>(stage_k, (T*)a.dK + head_off + (int64_t)kw0 * a.sn, a.sn, dk, a.tau, a.N - kw0);
+                               DROPOUT ? a.keep_scale : 1.f, a.N - kw0, D == 32 ? a.dvalid : D);
+    store_rows_coalesced<T, D>(stage_k, (T*)a.dK + head_off + (int64_t)kw0 * a.sn, a.sn, dk, a.tau, a.N - kw0,
+                               D == 32 ? a.dvalid : D);
   }
   if (!list_mode && last_round) return;
   __syncthreads();   // LDS is reused by the next key block

@@ -36,6 +36,7 @@ struct KArgs {
   int64_t sb, sh, sn;      // element strides of the [B,H,N,d] tensors
   int B, H, N, T;          // T = ceil(N / 128)
   int Nr;                  // 128 T: rows per head of the backward scratch vectors
+  int dvalid;              // head dimension of the tensors: 16 with the D = 32 kernels (columns 16..31 are zeros on chip), else D
   float tau;               // softmax scale
   float scale_log2;        // tau * log2(e)
   float keep_scale;        // 1 / (1 - p_drop)

@@ -78,8 +78,14 @@ __global__ __launch_bounds__(NT, 2) void fwd_kernel(const KArgs a) {
   // Q^T fragments (B operand): lane holds query qi, d = 16 kk + 8 g .. +7
   T8 qf[KK];
 #pragma unroll
-  for (int kk = 0; kk < KK; ++kk)
-    qf[kk] = *(const T8*)(Qg + (int64_t)qi * a.sn + 16 * kk + 8 * g);
+  for (int kk = 0; kk < KK; ++kk) {
+    if (D == 32 && 16 * kk + 8 * g >= a.dvalid) {   // head dimension 16: the upper columns are zeros
+#pragma unroll
+      for (int e = 0; e < 8; ++e) qf[kk][e] = (T)0.f;
+    } else {
+      qf[kk] = *(const T8*)(Qg + (int64_t)qi * a.sn + 16 * kk + 8 * g);
+    }
+  }
 
   f32x16 o[DB];
 #pragma unroll
@@ -105,7 +111,12 @@ __global__ __launch_bounds__(NT, 2) void fwd_kernel(const KArgs a) {
   TrOffsets<D> tro;
   tro.init();
   TileAsync<T, D, NT / 64> dma;
-  dma.init(a.sn, wave);
+  dma.init(a.sn, wave, D == 32 ? a.dvalid : D);
+  if (D == 32 && a.dvalid < D) {   // the copies leave columns >= 16 of the tile buffers untouched
+    zero_tiles(&Ks[0][0], 2 * BC * D);
+    zero_tiles(&Vs[0][0], 2 * BC * D);
+    __syncthreads();
+  }
 
   const float c = a.scale_log2;
   int jt = it.next();
@@ -271,13 +282,14 @@ __global__ __launch_bounds__(NT, 2) void fwd_kernel(const KArgs a) {
           f32x4 v;
 #pragma unroll
           for (int e = 0; e < 4; ++e) v[e] = o[db][4 * i4 + e] * inv;
-          *(f32x4*)(Og + 32 * db + 8 * i4 + 4 * g) = v;
+          if (D != 32 || 8 * i4 + 4 * g < a.dvalid) *(f32x4*)(Og + 32 * db + 8 * i4 + 4 * g) = v;
         }
     }
   } else {
     // coalesced row stores through the (now idle) tile buffers: two wavefronts per buffer
     T* stage = (wave < 2 ? &Ks[0][0] + wave * 32 * D : &Vs[0][0] + (wave - 2) * 32 * D);
-    store_rows_coalesced<T, D>(stage, (T*)a.O + head_off + (int64_t)q0 * a.sn, a.sn, o, inv, a.N - q0);
+    store_rows_coalesced<T, D>(stage, (T*)a.O + head_off + (int64_t)q0 * a.sn, a.sn, o, inv, a.N - q0,
+                               D == 32 ? a.dvalid : D);
   }
   }  // for pass
 }

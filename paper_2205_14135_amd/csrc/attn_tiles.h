@@ -82,25 +82,37 @@ __device__ __forceinline__ uint32_t lds_addr(const void* p) {
 
 // The tile copy: NW wavefronts (numbered 0..NW-1 by the caller) issue (D/8)/NW copy instructions each.
 // ROWS: rows of the tile (64 unless a kernel streams smaller tiles).
+// Head dimension 16 runs on the D = 32 kernels: the tensors' rows hold d_valid = 16 elements, the
+// lanes whose chunk lies beyond them copy nothing, and the kernel clears the tile buffers once
+// (zero_tiles below), so that columns 16..31 read as zeros.
 template <typename T, int D, int NW, int ROWS = 64> struct TileAsync {
   static constexpr int CPR = D / 8, RPC = 64 / CPR, NCOPY = ROWS / RPC, PER_WAVE = NCOPY / NW;
   static_assert(NCOPY % NW == 0, "copies must divide evenly over the wavefronts");
   uint32_t goff[PER_WAVE];   // byte offset of this lane's chunk inside a tile whose row 0 is at 0
   int wave;                  // (the host checks that 64 rows of the tensor span less than 2^31 bytes)
-  __device__ __forceinline__ void init(int64_t sn, int wave_index) {
+  uint32_t beyond;           // D = 32 only: bit p set if this lane's chunk of copy p is beyond d_valid
+  __device__ __forceinline__ void init(int64_t sn, int wave_index, int d_valid = D) {
     const int lane = threadIdx.x & 63;
     wave = wave_index;
+    beyond = 0;
 #pragma unroll
     for (int p = 0; p < PER_WAVE; ++p) {
       const int row = (wave * PER_WAVE + p) * RPC + lane / CPR;
-      goff[p] = (uint32_t)(((int64_t)row * sn + 8 * ((lane % CPR) ^ swz_bits<D>(row))) * (int64_t)sizeof(T));
+      const int chunk = (lane % CPR) ^ swz_bits<D>(row);
+      goff[p] = (uint32_t)(((int64_t)row * sn + 8 * chunk) * (int64_t)sizeof(T));
+      if (8 * chunk >= d_valid) beyond |= 1u << p;
     }
+  }
+  __device__ __forceinline__ bool skip(int p) const {
+    if constexpr (D == 32) return (beyond >> p) & 1u;
+    return false;
   }
   // g_row0 must be wavefront-uniform
   __device__ __forceinline__ void copy(const T* g_row0, const T* lds_tile) const {
     const uint32_t base = __builtin_amdgcn_readfirstlane(lds_addr(lds_tile) + (wave * PER_WAVE) * 1024);
 #pragma unroll
-    for (int p = 0; p < PER_WAVE; ++p) async_copy_b128(g_row0, goff[p], base + p * 1024);
+    for (int p = 0; p < PER_WAVE; ++p)
+      if (!skip(p)) async_copy_b128(g_row0, goff[p], base + p * 1024);
   }
   // The last tile of a tensor whose row count is not a multiple of 64: only rows_valid (>= 1) rows
   // exist; the LDS rows beyond them receive a copy of the last valid row (finite values that the
@@ -112,7 +124,7 @@ template <typename T, int D, int NW, int ROWS = 64> struct TileAsync {
 #pragma unroll
     for (int p = 0; p < PER_WAVE; ++p) {
       const int excess = max((wave * PER_WAVE + p) * RPC + lane_row - (rows_valid - 1), 0);   // rows past the last one
-      async_copy_b128(g_row0, goff[p] - (uint32_t)excess * row_bytes, base + p * 1024);
+      if (!skip(p)) async_copy_b128(g_row0, goff[p] - (uint32_t)excess * row_bytes, base + p * 1024);
     }
   }
   // tile whose first row is row0 of a tensor with n_rows rows (row0 < n_rows)
@@ -121,6 +133,17 @@ template <typename T, int D, int NW, int ROWS = 64> struct TileAsync {
     else copy_tail(g + (int64_t)row0 * sn, lds_tile, sn, n_rows - row0);
   }
 };
+
+// Clears n_elems (a multiple of 8 per thread pass) elements of LDS with all threads of the
+// workgroup; the caller synchronises before copies land in the buffer.
+template <typename T>
+__device__ __forceinline__ void zero_tiles(T* lds, int n_elems) {
+  typedef typename Vec<T>::x8 T8;
+  T8 z;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) z[i] = (T)0.f;
+  for (int i = 8 * (int)threadIdx.x; i < n_elems; i += 8 * (int)blockDim.x) *(T8*)(lds + i) = z;
+}
 
 // Per-lane LDS offsets for the transposing read of a swizzled tile (see attn_fwd.hip for the
 // access pattern): off[db][hi] addresses rows 4g + t (+8 if hi) of a 16-row chunk, d block db.
@@ -174,7 +197,7 @@ __device__ __forceinline__ void store_rows(T* dst_row, const f32x16 (&acc)[D / 3
 template <typename T, int D>
 __device__ __forceinline__ void store_rows_coalesced(T* stage, T* dst_row0, int64_t sn,
                                                      const f32x16 (&acc)[D / 32], float scale,
-                                                     int rows_valid = 32) {
+                                                     int rows_valid = 32, int cols_valid = D) {
   typedef typename Vec<T>::x4 T4;
   typedef typename Vec<T>::x8 T8;
   constexpr int CPR = D / 8;         // 16-byte chunks per row
@@ -195,7 +218,7 @@ __device__ __forceinline__ void store_rows_coalesced(T* stage, T* dst_row0, int6
   for (int p = 0; p < 32 / RPP; ++p) {
     const int row = p * RPP + lane / CPR, ch = lane % CPR;
     const T8 v = *(const T8*)(stage + row * D + 8 * (ch ^ (row & (CPR - 1))));
-    if (row < rows_valid) *(T8*)(dst_row0 + (int64_t)row * sn + 8 * ch) = v;
+    if (row < rows_valid && 8 * ch < cols_valid) *(T8*)(dst_row0 + (int64_t)row * sn + 8 * ch) = v;
   }
 }
 

@@ -62,7 +62,8 @@ def test_struct_layout_matches_c():
 @pytest.mark.parametrize("kw,code", [
     (dict(dtype=2), -3),
     (dict(d=96), -4),
-    (dict(d=16), -4),
+    (dict(d=8), -4),
+    (dict(d=48), -4),
     (dict(N=0), -2),
     (dict(N=-128), -2),
     (dict(B=0), -2),
