@@ -174,11 +174,11 @@ def run_gpu(cfg, steps, warmup, seed, mask_override=None, nsets=1):
         pp_items = B * H * ((n_qt + 1) // 2 if cfg["causal"] else n_qt)
         use_pp = (d == 128 and pp_items >= 256 and
                   (cfg["causal"] if cfg["p"] > 0 else (N >= 1024 or (cfg["causal"] and N >= 512))))
-    # dK/dV: the one-wavefront kernels at d <= 64 and (no mask, no dropout) at d = 128, else the
+    # dK/dV: the one-wavefront kernels at d <= 64 and (dense, no dropout) at d = 128, else the
     # role-split one (launch_dkv_rs())
     if d <= 64:
         dkv = "dkv_fr_kernel"
-    elif not cfg["sparse"] and not cfg["causal"] and cfg["p"] == 0:
+    elif not cfg["sparse"] and cfg["p"] == 0:
         dkv = "dkv_fr128_kernel"
     else:
         dkv = "dkv_rs_kernel"

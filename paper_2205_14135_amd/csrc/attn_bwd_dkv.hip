@@ -504,8 +504,8 @@ int launch_dkv_rs(const KArgs& a, int dtype, int d, bool causal, bool dropout, b
   // planning and the finish kernel).
   // (head dimension 16 exists in that kernel only)
   if (!sparse && d <= 64 && (!force_role_split() || a.dvalid < d)) return launch_dkv_fr(a, dtype, d, causal, dropout, false, 0, s);
-  // d = 128, no mask, no dropout: the one-wavefront kernel with the V block in LDS (attn_bwd_dkv_fr128.hip)
-  if (!sparse && d == 128 && !causal && !dropout && !force_role_split()) return launch_dkv_fr128(a, dtype, s);
+  // d = 128, dense, no dropout: the one-wavefront kernel with the V block in LDS (attn_bwd_dkv_fr128.hip)
+  if (!sparse && d == 128 && !dropout && !force_role_split()) return launch_dkv_fr128(a, dtype, causal, s);
   if (dtype == 0 && d == 32) return launch_td<_Float16, 32>(a, causal, dropout, sparse, s);
   if (dtype == 1 && d == 32) return launch_td<__bf16, 32>(a, causal, dropout, sparse, s);
   if (dtype == 0 && d == 64) return launch_td<_Float16, 64>(a, causal, dropout, sparse, s);

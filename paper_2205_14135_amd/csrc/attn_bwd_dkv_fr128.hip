@@ -1,5 +1,5 @@
-// dK / dV kernel for head dimension 128, dense problems without causal mask and without dropout,
-// in which one wavefront does all four tile products of its 32 keys (the arrangement of
+// dK / dV kernel for head dimension 128, dense problems without dropout, in which one wavefront
+// does all four tile products of its 32 keys (the arrangement of
 // attn_bwd_dkv_fr.hip carried to d = 128).
 //
 // Arithmetic: Algorithm 4 of the paper for one block of 128 keys, swept over 32-query tiles:
@@ -10,9 +10,10 @@
 // Q/dO double buffers 4 x 8 KB + V 32 KB = 64 KB per workgroup, two free-running workgroups of four
 // wavefronts per compute unit.  S and dP, and then dV and dK, are issued as alternating MFMA
 // streams, so that consecutive instructions write different accumulators.  Measured 6 % faster
-// than the role-split kernel of attn_bwd_dkv.hip at N = 4096 and 10 % at N = 1024; the causal form
-// of this kernel does not fit the register file, and dropout is not implemented: those problems
-// keep the role-split kernel.
+// than the role-split kernel of attn_bwd_dkv.hip at N = 4096 and 10 % at N = 1024.  Under the causal
+// mask a workgroup takes one key block (not a pair: the loop over a pair costs registers this
+// kernel does not have) and the blocks are dealt out heaviest first.  Dropout is not implemented:
+// those problems keep the role-split kernel.
 #include <type_traits>
 
 #include "attn_common.h"
@@ -25,7 +26,7 @@ constexpr int NT = 256;
 constexpr int QT = 32;    // queries per streamed tile
 constexpr int D = 128;
 
-template <typename T>
+template <typename T, bool CAUSAL>
 __global__ __launch_bounds__(NT, 2) void dkv_fr128_kernel(const KArgs a) {
   typedef typename Vec<T>::x8 T8;
   constexpr int KK = D / 16, DB = D / 32;
@@ -42,8 +43,20 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr128_kernel(const KArgs a) {
   const int n_kt = a.T;   // ceil(N / 128): the last key block may be ragged
   const int item = xcd_item(a.n_items, a.chunk);
   if (item < 0) return;
-  const int bh = item / n_kt;
-  const int kt = item % n_kt;
+  int bh = item / n_kt;
+  int kt = item % n_kt;
+  if constexpr (CAUSAL) {
+    // Key block k is visited by the query tiles from the diagonal on, so its work falls with k.
+    // The key blocks of a.group consecutive heads are dealt out together, heaviest first, so that
+    // the items a compute unit receives last are light ones (the host sizes the group so that the
+    // Q and dO of its heads, the L2 working set of an XCD, stay within 8 MiB).
+    const int n_heads = a.B * a.H;
+    const int grp0 = (bh / a.group) * a.group;             // first head of this group
+    const int gsz = min(a.group, n_heads - grp0);          // heads in it (the last group may be short)
+    const int within = (bh - grp0) * n_kt + kt;            // position inside the group's items
+    bh = grp0 + within % gsz;
+    kt = within / gsz;
+  }
   const int b = bh / a.H, h = bh % a.H;
   const int64_t head_off = (int64_t)b * a.sb + (int64_t)h * a.sh;
   const T* __restrict__ Qg = (const T*)a.Q + head_off;
@@ -71,7 +84,7 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr128_kernel(const KArgs a) {
     for (int i = 0; i < 16; ++i) { dv[db][i] = 0.f; dk[db][i] = 0.f; }
 
   const int len = a.klen ? min(max(a.klen[b], 0), a.N) : a.N;
-  const int first = 0;
+  const int first = CAUSAL ? kt * (128 / QT) : 0;   // causal: the tiles above the diagonal see none of these keys
   const int limit = kt * 128 >= len ? 0 : (len + QT - 1) / QT;
 
   TrOffsets<D> tro;
@@ -102,7 +115,12 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr128_kernel(const KArgs a) {
   auto tile_step = [&](int t, auto buf_c) {
     constexpr int buf = decltype(buf_c)::value;
     if (t + 1 < limit) fetch_tile(t + 1, buf ^ 1);
-    {
+    // causal: of the four tiles on the diagonal of the key block, wavefront w joins from the w-th
+    // on, and masks inside that one: query 8 i4 + 4 g + e of the tile sees this lane's key iff
+    // that number is >= kj - first query of the tile
+    const int i0 = t * QT;
+    const int hidden_below = CAUSAL && i0 == kw0 ? r - 4 * g : -(1 << 30);
+    if (!CAUSAL || i0 >= kw0) {
       const T* Qt = Qs0 + buf * QT * D;
       const T* Gt = Gs0 + buf * QT * D;
       // ---- S = Q K^T and dP = dO V^T (32 queries x 32 keys each) as one stream of alternating
@@ -146,6 +164,7 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr128_kernel(const KArgs a) {
         for (int e = 0; e < 4; ++e) {
           const int i = 4 * i4 + e;
           float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], c, -l4[e]));
+          if (CAUSAL && 8 * i4 + e < hidden_below) p = 0.f;
           s[i] = p;
           pf[i4 >> 1][4 * (i4 & 1) + e] = (T)p;
         }
@@ -197,16 +216,23 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr128_kernel(const KArgs a) {
 }
 
 template <typename T>
-int launch_t(const KArgs& a, hipStream_t s) {
+int launch_t(const KArgs& a_in, bool causal, hipStream_t s) {
+  KArgs a = a_in;
+  {
+    const int64_t tile_bytes = 2 * (int64_t)a.N * D * (int64_t)sizeof(T);   // Q and dO of one head
+    const int64_t fit = ((int64_t)8 << 20) / tile_bytes;
+    a.group = (int)(fit < 1 ? 1 : (fit > 8 ? 8 : fit));
+  }
   const dim3 grid(kXcds * a.chunk), block(NT);
-  hipLaunchKernelGGL((dkv_fr128_kernel<T>), grid, block, 0, s, a);
+  if (causal) hipLaunchKernelGGL((dkv_fr128_kernel<T, true>), grid, block, 0, s, a);
+  else hipLaunchKernelGGL((dkv_fr128_kernel<T, false>), grid, block, 0, s, a);
   return (int)hipGetLastError();
 }
 
 }  // namespace
 
-int launch_dkv_fr128(const KArgs& a, int dtype, hipStream_t s) {
-  return dtype == 0 ? launch_t<_Float16>(a, s) : launch_t<__bf16>(a, s);
+int launch_dkv_fr128(const KArgs& a, int dtype, bool causal, hipStream_t s) {
+  return dtype == 0 ? launch_t<_Float16>(a, causal, s) : launch_t<__bf16>(a, causal, s);
 }
 
 }  // namespace attn

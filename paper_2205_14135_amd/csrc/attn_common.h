@@ -67,7 +67,7 @@ int launch_dkv_rs(const KArgs& a, int dtype, int d, bool causal, bool dropout, b
 int launch_dkv_fr(const KArgs& a, int dtype, int d, bool causal, bool dropout, bool sparse, int extra_groups,
                   hipStream_t s);
 // the same at d = 128 for dense problems without causal mask and dropout (attn_bwd_dkv_fr128.hip)
-int launch_dkv_fr128(const KArgs& a, int dtype, hipStream_t s);
+int launch_dkv_fr128(const KArgs& a, int dtype, bool causal, hipStream_t s);
 // dense forward with two wavefront groups in ping-pong (attn_fwd_pp.hip); sets its own work items
 int launch_fwd_pp(const KArgs& a, int dtype, int d, bool causal, bool dropout, hipStream_t s);
 // MFMA-only kernel for measuring the sustained matrix rate (attn_probe.hip); *flops = FLOPs launched
