@@ -29,9 +29,9 @@ def _rel(a, b):
     return float((a.float() - b.float()).norm() / b.float().norm())
 
 
-@pytest.mark.parametrize("causal,p", [(False, 0.0), (True, 0.0), (True, 0.2)])
-def test_gradients_match_pytorch_autograd(causal, p):
-    B, H, N, d = 2, 3, 200, 64     # N is not a multiple of the tile on purpose
+@pytest.mark.parametrize("causal,p,d", [(False, 0.0, 64), (True, 0.0, 64), (True, 0.2, 64), (True, 0.2, 16), (False, 0.0, 128)])
+def test_gradients_match_pytorch_autograd(causal, p, d):
+    B, H, N = 2, 3, 200     # N is not a multiple of the tile on purpose
     t = inputs.gaussian_tensors(B, H, N, d, "bf16", inputs.BASE_SEED + 1200)
     tau = 1 / math.sqrt(d)
     seed, offset = inputs.BASE_DROPOUT_SEED + 12, 7
