@@ -372,24 +372,32 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
 }
 
 // Block-sparse preparation, step 1: kept blocks per mask column (rows >= column under a causal
-// mask) and their total.  One 64-thread group per (bh, kt).
-__global__ __launch_bounds__(64) void sparse_count_kernel(const KArgs a) {
-  const int item = blockIdx.x;
+// mask) and their total.  One 1024-thread group per (bh, 64 consecutive columns): thread = (column,
+// one of 16 row groups), so that the 64 lanes of a wavefront read 64 consecutive mask bytes of one
+// row (a thread per column entry of one column reads one byte per 64-byte line).
+constexpr int kCountRowGroups = 16;
+__global__ __launch_bounds__(64 * kCountRowGroups) void sparse_count_kernel(const KArgs a) {
+  __shared__ int part[kCountRowGroups][64];
   const int n_kt = a.T;
-  const int bh = item / n_kt, kt = item % n_kt;
+  const int n_cg = (n_kt + 63) / 64;
+  const int bh = blockIdx.x / n_cg, cg = blockIdx.x % n_cg;
   const int h = bh % a.H;
-  const uint8_t* col = a.mask + (int64_t)h * a.mask_sh + kt;
+  const int c = threadIdx.x & 63, rg = threadIdx.x >> 6;
+  const int kt = cg * 64 + c;
   const int len = a.klen ? min(max(a.klen[bh / a.H], 0), a.N) : a.N;
-  const int first = a.causal ? kt : 0;                                     // same row range as the
-  const int limit = kt * 128 >= len ? 0 : min(a.T, (len + 127) / 128);     // tile iterator of dkv_rs_kernel
   int cnt = 0;
-  for (int base = first; base < limit; base += 64) {
-    const int blk = base + (int)threadIdx.x;
-    const bool on = blk < limit && col[(int64_t)blk * a.T] != 0;
-    cnt += __builtin_popcountll(__ballot(on));
+  if (kt < n_kt) {
+    const uint8_t* col = a.mask + (int64_t)h * a.mask_sh + kt;
+    const int first = a.causal ? kt : 0;                                     // same row range as the
+    const int limit = kt * 128 >= len ? 0 : min(a.T, (len + 127) / 128);     // tile iterators of the dK/dV kernels
+    for (int blk = first + rg; blk < limit; blk += kCountRowGroups) cnt += col[(int64_t)blk * a.T] != 0;
   }
-  if (threadIdx.x == 0) {
-    a.colcnt[item] = cnt;
+  part[rg][c] = cnt;
+  __syncthreads();
+  if (rg == 0 && kt < n_kt) {
+#pragma unroll
+    for (int g = 1; g < kCountRowGroups; ++g) cnt += part[g][c];
+    a.colcnt[bh * n_kt + kt] = cnt;
     if (cnt > 0) atomicAdd(a.seglist + 1, cnt);
   }
 }
@@ -454,7 +462,7 @@ int launch_td(KArgs a, bool causal, bool dropout, bool sparse, hipStream_t s) {
   const int cols = a.B * a.H * a.T;
   if (sparse) {
     a.causal = causal;
-    hipLaunchKernelGGL(sparse_count_kernel, dim3(cols), dim3(64), 0, s, a);
+    hipLaunchKernelGGL(sparse_count_kernel, dim3(a.B * a.H * ((a.T + 63) / 64)), dim3(64 * kCountRowGroups), 0, s, a);
     hipLaunchKernelGGL((sparse_plan_kernel<D>), dim3(cols), dim3(64), 0, s, a);
     const int e = (int)hipGetLastError();
     if (e != 0) return e;
