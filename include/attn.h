@@ -38,6 +38,13 @@
  * nothing outside the [B,H,N,d] tensors is read or written), N a multiple of
  * 128 for the block-sparse ones; tau finite and > 0; 0 <= p_drop < 1;
  * mask_block == 128.
+ *
+ * Which kernel a call takes depends on head dimension, length, masks and the
+ * number of heads; every choice computes the same operation to the same
+ * tolerance.  Two environment variables, read on every call, override the choice
+ * for comparisons: ATTN_FWD_VARIANT=base|pp (free-running or two-group forward
+ * kernel, where both exist) and ATTN_DKV_VARIANT=rs (role-split dK/dV kernel
+ * everywhere it exists).  Unset, the library picks by measurement.
  */
 #ifndef ATTN_H_
 #define ATTN_H_
