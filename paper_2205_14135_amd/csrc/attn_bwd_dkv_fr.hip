@@ -27,10 +27,28 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr_kernel(const KArgs a) {
   typedef typename Vec<T>::x8 T8;
   constexpr int KK = D / 16, DB = D / 32;
   static_assert(D <= 64, "the accumulators of both gradients must fit one wavefront");
-  __shared__ __attribute__((aligned(16))) T Qs[2][TILE * D];
-  __shared__ __attribute__((aligned(16))) T Gs[2][TILE * D];      // dO tiles
-  __shared__ __attribute__((aligned(16))) float Ls[2][TILE];      // base-2 row statistic
-  __shared__ __attribute__((aligned(16))) float Ds[2][TILE];      // -D_i
+  // Tile buffers, double buffered: Q tiles Qs0 + buf TILE D, dO tiles Gs0 + buf TILE D, base-2 row
+  // statistic Ls0 + buf TILE, -D_i Ds0 + buf TILE.  The plain dense kernel (no mask, no dropout)
+  // unrolls its tile loop by two, so that the buffer index is a constant, and keeps all of them in
+  // one LDS block (row vectors first): every LDS address is then a per-lane register plus an
+  // immediate.  The other forms have no registers for two copies of the loop body and keep the
+  // separate arrays (the form their register allocation is tuned to).
+  constexpr int UNROLL = (!CAUSAL && !DROPOUT && !SPARSE) ? 2 : 1;
+  T *Qs0, *Gs0;
+  float *Ls0, *Ds0;
+  if constexpr (UNROLL == 2) {
+    __shared__ __attribute__((aligned(16))) unsigned char smem[4 * TILE * sizeof(float) + 4 * TILE * D * sizeof(T)];
+    Ls0 = (float*)smem;
+    Ds0 = Ls0 + 2 * TILE;
+    Qs0 = (T*)(smem + 4 * TILE * sizeof(float));
+    Gs0 = Qs0 + 2 * TILE * D;
+  } else {
+    __shared__ __attribute__((aligned(16))) T Qs[2 * TILE * D];
+    __shared__ __attribute__((aligned(16))) T Gs[2 * TILE * D];
+    __shared__ __attribute__((aligned(16))) float Ls[2 * TILE];
+    __shared__ __attribute__((aligned(16))) float Ds[2 * TILE];
+    Qs0 = Qs; Gs0 = Gs; Ls0 = Ls; Ds0 = Ds;
+  }
 
   const int n_kt = a.T;   // ceil(N / 128): the last key block may be ragged
   // Work assignment.  Dense: one key block per workgroup; under the causal mask key block k is
@@ -124,15 +142,15 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr_kernel(const KArgs a) {
   TileAsync<T, D, 4> dma;
   dma.init(a.sn, wave, D == 32 ? a.dvalid : D);
   if (D == 32 && a.dvalid < D) {   // the copies leave columns >= 16 of the tile buffers untouched
-    zero_tiles(&Qs[0][0], 2 * TILE * D);   // (again in every round: the buffers staged output rows)
-    zero_tiles(&Gs[0][0], 2 * TILE * D);
+    zero_tiles(Qs0, 2 * TILE * D);   // (again in every round: the buffers staged output rows)
+    zero_tiles(Gs0, 2 * TILE * D);
     __syncthreads();
   }
   auto fetch_tile = [&](int t, int buf) {
-    dma.copy_rows(Qg, a.sn, t * TILE, a.N, Qs[buf]);
-    dma.copy_rows(Gg, a.sn, t * TILE, a.N, Gs[buf]);
-    if (wave == 1) async_copy_b32(Lg + t * TILE + lane, __builtin_amdgcn_readfirstlane(lds_addr(Ls[buf])));
-    if (wave == 2) async_copy_b32(Dg + t * TILE + lane, __builtin_amdgcn_readfirstlane(lds_addr(Ds[buf])));
+    dma.copy_rows(Qg, a.sn, t * TILE, a.N, Qs0 + buf * TILE * D);
+    dma.copy_rows(Gg, a.sn, t * TILE, a.N, Gs0 + buf * TILE * D);
+    if (wave == 1) async_copy_b32(Lg + t * TILE + lane, __builtin_amdgcn_readfirstlane(lds_addr(Ls0 + buf * TILE)));
+    if (wave == 2) async_copy_b32(Dg + t * TILE + lane, __builtin_amdgcn_readfirstlane(lds_addr(Ds0 + buf * TILE)));
   };
   const float c = a.scale_log2;
 
@@ -224,18 +242,21 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr_kernel(const KArgs a) {
   };
 
   // ---- pipeline over the query tiles of this key block: tile t + 1 streams in while t is used
-  int buf = 0;
+  int buf_rt = 0;
   int t = it.next();
   if (t >= 0) fetch_tile(t, 0);
   wait_async_copies();
   __syncthreads();
   while (t >= 0) {
+#pragma unroll
+  for (int u = 0; u < UNROLL; ++u) {
+    const int buf = UNROLL == 2 ? u : buf_rt;
     const int t_next = it.next();
     if (t_next >= 0) fetch_tile(t_next, buf ^ 1);
     const int i0 = t * TILE;
     if (!CAUSAL || i0 + TILE - 1 >= kw0) {
       f32x16 s[2], dp[2];
-      row_product(Qs[buf], kf, false, nullptr, s);                // S = Q K^T
+      row_product(Qs0 + buf * TILE * D, kf, false, nullptr, s);                // S = Q K^T
       uint32_t kw[2][4] = {{0, 0, 0, 0}, {0, 0, 0, 0}};
       if constexpr (DROPOUT) keep_words(draw_keep(i0), kw);
       if (kw0 + 32 > len) {   // this wavefront holds padded keys: their logits become -inf, hence P = 0
@@ -251,7 +272,7 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr_kernel(const KArgs a) {
       for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
         for (int i4 = 0; i4 < 4; ++i4) {
-          const f32x4 l4 = *(const f32x4*)(&Ls[buf][32 * qb + 8 * i4 + 4 * g]);
+          const f32x4 l4 = *(const f32x4*)(Ls0 + buf * TILE + 32 * qb + 8 * i4 + 4 * g);
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             const int i = 4 * i4 + e;
@@ -267,16 +288,16 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr_kernel(const KArgs a) {
             }
           }
         }
-      col_product(Gs[buf], pf, dv);                          // dV^T += dO^T P_dropped
+      col_product(Gs0 + buf * TILE * D, pf, dv);                          // dV^T += dO^T P_dropped
       // dP = dO V^T; without dropout it starts from -D, so the result is dP - D
-      row_product(Gs[buf], vf, !DROPOUT, Ds[buf], dp);
+      row_product(Gs0 + buf * TILE * D, vf, !DROPOUT, Ds0 + buf * TILE, dp);
       T8 dsf[4];
 #pragma unroll
       for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
         for (int i4 = 0; i4 < 4; ++i4) {
           f32x4 d4 = {0.f, 0.f, 0.f, 0.f};
-          if constexpr (DROPOUT) d4 = *(const f32x4*)(&Ds[buf][32 * qb + 8 * i4 + 4 * g]);   // -D_i
+          if constexpr (DROPOUT) d4 = *(const f32x4*)(Ds0 + buf * TILE + 32 * qb + 8 * i4 + 4 * g);   // -D_i
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             const int i = 4 * i4 + e;
@@ -289,12 +310,14 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr_kernel(const KArgs a) {
             dsf[cc][tt] = (T)(s[qb][i] * dpv);
           }
         }
-      col_product(Qs[buf], dsf, dk);                         // dK^T += Q^T dS
+      col_product(Qs0 + buf * TILE * D, dsf, dk);                         // dK^T += Q^T dS
     }
     wait_async_copies();
     __syncthreads();   // the next tile has landed, and everyone is done with this buffer
-    buf ^= 1;
+    buf_rt ^= 1;
     t = t_next;
+    if (t < 0) break;
+  }
   }
 
   if (SPARSE && heavy) {
@@ -312,8 +335,8 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr_kernel(const KArgs a) {
       }
   } else {
     // the loop ends on a barrier (or never touched LDS): the tile buffers stage the output rows
-    T* stage_v = &Qs[0][0] + wave * 32 * D;   // 4 wavefronts x 32 rows = the two Q buffers
-    T* stage_k = &Gs[0][0] + wave * 32 * D;
+    T* stage_v = Qs0 + wave * 32 * D;   // 4 wavefronts x 32 rows = the two Q buffers
+    T* stage_k = Gs0 + wave * 32 * D;
     store_rows_coalesced<T, D>(stage_v, (T*)a.dV + head_off + (int64_t)kw0 * a.sn, a.sn, dv,
                                DROPOUT ? a.keep_scale : 1.f, a.N - kw0, D == 32 ? a.dvalid : D);
     store_rows_coalesced<T, D>(stage_k, (T*)a.dK + head_off + (int64_t)kw0 * a.sn, a.sn, dk, a.tau, a.N - kw0,
