@@ -27,11 +27,17 @@
  *     NULL for the default stream), never synchronise the device, and may be
  *     issued concurrently from several host threads.
  *   - Outputs are fully overwritten; the caller need not clear them.
- *   - A query row that sees no key (possible only through a block mask) gets
- *     O = 0, LSE = -inf and contributes zero gradients.
- *   - All argument checks happen on the host before anything is launched.
+ *   - A query row that sees no key (through a block mask, or a padded position
+ *     under key_lengths) gets O = 0, LSE = -inf and contributes zero gradients.
+ *   - All argument checks happen on the host before anything is launched:
+ *     sizes, strides (rows 16-byte aligned, non-overlapping: the axes of size
+ *     > 1 must nest by stride, as in [B,H,N,d] or a [B,N,H,d] view), tensor
+ *     pointers (non-NULL, 16-byte aligned), scale, dropout, mask, workspace.
  *     Functions return ATTN_OK (0) or a negative attn_status; they never
  *     abort, throw, or print.
+ *   - Every element of the input tensors must be finite, padded positions
+ *     (under key_lengths) included: they enter the matrix products with weight
+ *     zero, and 0 * inf is not zero.
  *
  * Supported in this version: d in {16, 32, 64, 128}; any N >= 1 for the dense entry
  * points (a last block of fewer than 128 tokens is handled inside the kernels:
@@ -41,10 +47,10 @@
  *
  * Which kernel a call takes depends on head dimension, length, masks and the
  * number of heads; every choice computes the same operation to the same
- * tolerance.  Two environment variables, read on every call, override the choice
- * for comparisons: ATTN_FWD_VARIANT=base|pp (free-running or two-group forward
- * kernel, where both exist) and ATTN_DKV_VARIANT=rs (role-split dK/dV kernel
- * everywhere it exists).  Unset, the library picks by measurement.
+ * tolerance.  attn_debug_set_variant overrides the choice for comparisons and
+ * tests; its initial values come from two environment variables read once, when
+ * the first call needs them: ATTN_FWD_VARIANT=base|pp and ATTN_DKV_VARIANT=rs|fr.
+ * Unset, the library picks by measurement.
  */
 #ifndef ATTN_H_
 #define ATTN_H_
@@ -59,7 +65,7 @@ extern "C" {
 typedef enum {
   ATTN_OK = 0,
   ATTN_ERR_NULL = -1,       /* a required pointer is NULL */
-  ATTN_ERR_SHAPE = -2,      /* B, H, N out of range, bad strides, block-sparse with N % 128 != 0 */
+  ATTN_ERR_SHAPE = -2,      /* B, H, N out of range, bad strides, misaligned tensor, block-sparse with N % 128 != 0 */
   ATTN_ERR_DTYPE = -3,      /* dtype is neither ATTN_FP16 nor ATTN_BF16 */
   ATTN_ERR_HEADDIM = -4,    /* d not in {16, 32, 64, 128} */
   ATTN_ERR_DROPOUT_P = -5,  /* p_drop not in [0, 1) or NaN */
@@ -115,9 +121,10 @@ int attn_fwd(const attn_params* p, const void* Q, const void* K, const void* V,
              void* O, float* LSE);
 
 /*
- * Bytes of scratch that attn_bwd / attn_blocksparse_bwd need for these
- * params: linear in B*H*N*d, never quadratic in N.  Returns 0 if the params
- * are invalid.
+ * Bytes of scratch that attn_bwd needs for these params: two floats per query
+ * row (D_i of Eq. (4), Appendix B.2, and the row statistic in base 2), i.e. the
+ * O(N) additional memory of Theorem 1; never quadratic in N.  Returns 0 if the
+ * params are invalid.
  */
 size_t attn_bwd_workspace_bytes(const attn_params* p);
 
@@ -200,6 +207,15 @@ int attn_debug_dropout_mask(const attn_params* p, uint8_t* keep);
  * floating-point operations launched.  iters in [1, 2^20].  Asynchronous.
  */
 int attn_debug_mfma_rate(int32_t dtype, int32_t iters, float* sink, void* stream, double* flops);
+
+/*
+ * Test and comparison hook, outside the paper's operation: which kernel serves the calls that
+ * have a choice.  fwd_variant: 0 = by measurement, 1 = free-running forward kernel, 2 = two-group
+ * forward kernel (where both exist).  dkv_variant: 0 = by measurement, 1 = role-split dK/dV kernel
+ * wherever it exists, 2 = one-wavefront dK/dV kernels only (never the 64-keys-per-wavefront one).
+ * -1 leaves a setting unchanged.  Process-wide and thread-safe; affects calls issued afterwards.
+ */
+int attn_debug_set_variant(int32_t fwd_variant, int32_t dkv_variant);
 
 /* Static, human-readable text for a status code. */
 const char* attn_strerror(int status);

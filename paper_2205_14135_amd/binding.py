@@ -19,7 +19,7 @@ ATTN_FP16, ATTN_BF16 = 0, 1
 
 SYMBOLS = (
     "attn_fwd", "attn_bwd_workspace_bytes", "attn_blocksparse_bwd_workspace_bytes", "attn_bwd", "attn_blocksparse_fwd",
-    "attn_blocksparse_bwd", "attn_bwd_timed", "attn_debug_dropout_mask", "attn_debug_mfma_rate", "attn_strerror",
+    "attn_blocksparse_bwd", "attn_bwd_timed", "attn_debug_dropout_mask", "attn_debug_mfma_rate", "attn_debug_set_variant", "attn_strerror",
     "attn_version",
 )
 
@@ -78,6 +78,8 @@ def load() -> ctypes.CDLL:
     lib.attn_debug_dropout_mask.restype = ctypes.c_int
     lib.attn_debug_mfma_rate.argtypes = [i32, i32, vp, vp, ctypes.POINTER(ctypes.c_double)]
     lib.attn_debug_mfma_rate.restype = ctypes.c_int
+    lib.attn_debug_set_variant.argtypes = [i32, i32]
+    lib.attn_debug_set_variant.restype = ctypes.c_int
     lib.attn_strerror.argtypes = [ctypes.c_int]
     lib.attn_strerror.restype = ctypes.c_char_p
     lib.attn_version.argtypes = []
@@ -273,3 +275,14 @@ def attn_debug_mfma_rate(dtype: str, iters: int, sink: torch.Tensor) -> float:
     _check(load().attn_debug_mfma_rate(code, int(iters), _ptr(sink), stream, ctypes.byref(fl)),
            "attn_debug_mfma_rate")
     return float(fl.value)
+
+
+FWD_VARIANTS = {"auto": 0, "base": 1, "pp": 2}
+DKV_VARIANTS = {"auto": 0, "rs": 1, "fr": 2}
+
+
+def attn_debug_set_variant(fwd: Optional[str] = None, dkv: Optional[str] = None) -> None:
+    """Overrides the kernel choice for the calls that follow (None leaves a setting unchanged)."""
+    f = -1 if fwd is None else FWD_VARIANTS[fwd]
+    k = -1 if dkv is None else DKV_VARIANTS[dkv]
+    _check(load().attn_debug_set_variant(f, k), "attn_debug_set_variant")

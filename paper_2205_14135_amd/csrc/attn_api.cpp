@@ -2,6 +2,9 @@
 #include "../../include/attn.h"
 #include "attn_common.h"
 
+#include <algorithm>
+#include <atomic>
+#include <cstdlib>
 #include <cmath>
 #include <cstring>
 
@@ -39,6 +42,23 @@ int check_params(const attn_params* p, Checked* out) {
   // rows must start on 16-byte boundaries for the vector loads
   if (sn < p->d || sn % 8 != 0 || sh % 8 != 0 || sb % 8 != 0 || sh < 0 || sb < 0) return ATTN_ERR_SHAPE;
   if (sn > ((int64_t)1 << 23)) return ATTN_ERR_SHAPE;   // the tile copies address 64 rows with 32-bit byte offsets
+  // Output rows must not alias: the axes of size > 1, taken by increasing stride, must nest (each
+  // stride at least the extent of the axis below it; the innermost at least one row).  This admits
+  // head-major [B,H,N,d], token-major [B,N,H,d] views and padded rows, and rejects zero strides.
+  {
+    int64_t st[3] = {sn, sh, sb};
+    int64_t sz[3] = {p->N, p->H, p->B};
+    for (int i = 0; i < 3; ++i)
+      for (int j = i + 1; j < 3; ++j)
+        if (st[j] < st[i]) { std::swap(st[i], st[j]); std::swap(sz[i], sz[j]); }
+    int64_t extent = p->d;
+    for (int i = 0; i < 3; ++i) {
+      if (sz[i] == 1) continue;
+      if (st[i] < extent) return ATTN_ERR_SHAPE;
+      if (st[i] > ((int64_t)1 << 50) / sz[i]) return ATTN_ERR_SHAPE;
+      extent = st[i] * sz[i];
+    }
+  }
   if (!(p->dropout_p >= 0.0f && p->dropout_p < 1.0f)) return ATTN_ERR_DROPOUT_P;
   if (!std::isfinite(p->softmax_scale) || !(p->softmax_scale > 0.0f)) return ATTN_ERR_SCALE;
 
@@ -93,12 +113,20 @@ WsLayout ws_layout(const attn_params* p) {
   return w;
 }
 
+// every [B,H,N,d] tensor is read and written in 16-byte pieces
+bool aligned16(std::initializer_list<const void*> ptrs) {
+  for (const void* q : ptrs)
+    if (((uintptr_t)q & 15u) != 0) return false;
+  return true;
+}
+
 int fwd_common(const attn_params* p, const uint8_t* mask, int64_t mask_sh, bool sparse,
                const void* Q, const void* K, const void* V, void* O, float* LSE) {
   Checked c;
   const int st = check_params(p, &c);
   if (st != ATTN_OK) return st;
   if (!Q || !K || !V || !O || !LSE) return ATTN_ERR_NULL;
+  if (!aligned16({Q, K, V, O}) || ((uintptr_t)LSE & 3u) != 0) return ATTN_ERR_SHAPE;
   c.k.Q = Q; c.k.K = K; c.k.V = V; c.k.O = O; c.k.LSE = LSE;
   c.k.mask = mask; c.k.mask_sh = mask_sh;
   set_items(c.k, c.k.T);
@@ -114,6 +142,7 @@ int bwd_common(const attn_params* p, const uint8_t* mask, int64_t mask_sh, bool 
   const int st = check_params(p, &c);
   if (st != ATTN_OK) return st;
   if (!Q || !K || !V || !O || !dO || !LSE || !dQ || !dK || !dV) return ATTN_ERR_NULL;
+  if (!aligned16({Q, K, V, O, dO, dQ, dK, dV}) || ((uintptr_t)LSE & 3u) != 0) return ATTN_ERR_SHAPE;
   const size_t need = sparse ? attn_blocksparse_bwd_workspace_bytes(p) : attn_bwd_workspace_bytes(p);
   if (ws == nullptr || ((uintptr_t)ws & 255u) != 0 || ws_bytes < need) return ATTN_ERR_WORKSPACE;
   c.k.Q = Q; c.k.K = K; c.k.V = V; c.k.O = const_cast<void*>(O); c.k.LSE = const_cast<float*>(LSE);
@@ -141,7 +170,37 @@ int bwd_common(const attn_params* p, const uint8_t* mask, int64_t mask_sh, bool 
   return e == 0 ? ATTN_OK : ATTN_ERR_LAUNCH;
 }
 
+// Kernel-choice overrides: set through attn_debug_set_variant; until then the values of
+// ATTN_FWD_VARIANT (base | pp) and ATTN_DKV_VARIANT (rs | fr), read once.
+std::atomic<int> g_fwd_variant{-1}, g_dkv_variant{-1};
+int env_choice(const char* name, char c1, char c2) {
+  const char* v = std::getenv(name);
+  if (v == nullptr) return 0;
+  return v[0] == c1 ? 1 : (v[0] == c2 ? 2 : 0);
+}
+
 }  // namespace
+
+namespace attn {
+int fwd_variant() {
+  int v = g_fwd_variant.load(std::memory_order_relaxed);
+  if (v < 0) {
+    v = env_choice("ATTN_FWD_VARIANT", 'b', 'p');
+    int expected = -1;
+    if (!g_fwd_variant.compare_exchange_strong(expected, v)) v = expected;
+  }
+  return v;
+}
+int dkv_variant() {
+  int v = g_dkv_variant.load(std::memory_order_relaxed);
+  if (v < 0) {
+    v = env_choice("ATTN_DKV_VARIANT", 'r', 'f');
+    int expected = -1;
+    if (!g_dkv_variant.compare_exchange_strong(expected, v)) v = expected;
+  }
+  return v;
+}
+}  // namespace attn
 
 extern "C" {
 
@@ -226,13 +285,20 @@ int attn_debug_mfma_rate(int32_t dtype, int32_t iters, float* sink, void* stream
   return e == 0 ? ATTN_OK : ATTN_ERR_LAUNCH;
 }
 
+int attn_debug_set_variant(int32_t fwd_variant, int32_t dkv_variant) {
+  if (fwd_variant < -1 || fwd_variant > 2 || dkv_variant < -1 || dkv_variant > 2) return ATTN_ERR_SHAPE;
+  if (fwd_variant >= 0) g_fwd_variant.store(fwd_variant);
+  if (dkv_variant >= 0) g_dkv_variant.store(dkv_variant);
+  return ATTN_OK;
+}
+
 const char* attn_strerror(int status) {
   switch (status) {
     case ATTN_OK: return "ok";
     case ATTN_ERR_NULL: return "a required pointer is NULL";
-    case ATTN_ERR_SHAPE: return "unsupported shape or strides (block-sparse: N must be a multiple of 128)";
+    case ATTN_ERR_SHAPE: return "unsupported shape, strides or tensor alignment (16 bytes; block-sparse: N must be a multiple of 128)";
     case ATTN_ERR_DTYPE: return "dtype must be ATTN_FP16 or ATTN_BF16";
-    case ATTN_ERR_HEADDIM: return "head dimension must be 32, 64 or 128";
+    case ATTN_ERR_HEADDIM: return "head dimension must be 16, 32, 64 or 128";
     case ATTN_ERR_DROPOUT_P: return "dropout_p must be in [0, 1)";
     case ATTN_ERR_SCALE: return "softmax_scale must be finite and positive";
     case ATTN_ERR_WORKSPACE: return "workspace is NULL, not 256-byte aligned, or too small";

@@ -451,11 +451,8 @@ __global__ __launch_bounds__(256) void sparse_finish_kernel(const KArgs a) {
   }
 }
 
-// ATTN_DKV_VARIANT=rs keeps the role-split kernel at every head dimension (bench-time comparison)
-bool force_role_split() {
-  const char* v = getenv("ATTN_DKV_VARIANT");   // read on every call: tests switch it in-process
-  return v != nullptr && v[0] == 'r';
-}
+// dK/dV override 1 keeps the role-split kernel at every head dimension (comparisons and tests)
+bool force_role_split() { return dkv_variant() == 1; }
 
 template <typename T, int D>
 int launch_td(KArgs a, bool causal, bool dropout, bool sparse, hipStream_t s) {

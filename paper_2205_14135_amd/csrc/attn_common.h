@@ -55,6 +55,12 @@ enum { kXcds = 8, kMaskBlock = 128 };
 // kSegBlocks blocks (at most kMaxSegs), one workgroup each, summed with fp32 atomics.
 enum { kHeavyBlocks = 24, kSegBlocks = 12, kMaxSegs = 32, kSegHeader = 8, kComputeUnits = 256 };
 
+// Kernel-choice overrides (attn_debug_set_variant; initial values from the environment, read once
+// when first needed).  fwd: 0 = by measurement, 1 = free-running kernel, 2 = two-group kernel;
+// dkv: 0 = by measurement, 1 = role-split kernel wherever it exists, 2 = the 64-key kernel is not used.
+int fwd_variant();
+int dkv_variant();
+
 // Launchers (defined in the .hip files).  dtype: 0 fp16, 1 bf16.  Return hipError_t as int.
 int launch_fwd(const KArgs& a, int dtype, int d, bool causal, bool dropout, bool sparse, hipStream_t s);
 // ev: nullptr, or four events: two recorded before the first launch, one after the dQ kernel, one after dK/dV.

@@ -358,16 +358,15 @@ int launch_fwd(const KArgs& a, int dtype, int d, bool causal, bool dropout, bool
   //   and only if its 256-row work items (pairs of them under the causal mask) are at least as
   //     many as the compute units: a problem with few heads would leave half of the chip idle.
   // At d <= 64 the vector ALU work dominates and this file's kernel measured faster at every N;
-  // block-sparse problems always take it.  ATTN_FWD_VARIANT=base|pp overrides the choice
-  // (bench-time comparison).
-  const char* forced = getenv("ATTN_FWD_VARIANT");   // read on every call: tests switch it in-process
-  const char variant = forced != nullptr ? forced[0] : 'a';
+  // block-sparse problems always take it.  attn_debug_set_variant overrides the choice
+  // (comparisons and tests).
+  const int variant = fwd_variant();
   const int n_qt256 = (a.N + 255) / 256;
   const int64_t pp_items = (int64_t)a.B * a.H * (causal ? (n_qt256 + 1) / 2 : n_qt256);
   bool use_pp = d == 128 && pp_items >= kComputeUnits &&
                 (dropout ? causal : (a.N >= 1024 || (causal && a.N >= 512)));
-  if (variant == 'b') use_pp = false;
-  if (variant == 'p' && d != 32) use_pp = true;
+  if (variant == 1) use_pp = false;
+  if (variant == 2 && d != 32) use_pp = true;
   if (!sparse && use_pp) return launch_fwd_pp(a, dtype, d, causal, dropout, s);
   if (dtype == 0 && d == 32) return launch_fwd_td<_Float16, 32>(a, causal, dropout, sparse, s);
   if (dtype == 1 && d == 32) return launch_fwd_td<__bf16, 32>(a, causal, dropout, sparse, s);

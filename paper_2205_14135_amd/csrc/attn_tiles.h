@@ -25,12 +25,12 @@ __device__ __forceinline__ int lane_id_here() {
 // wait for the copy, and with run-time buffer indices every read might; a copy issued this way
 // stays in flight until the caller waits for it with wait_async_copies() (which it must do,
 // followed by a workgroup barrier, before any wavefront reads the tile).  lds_byte_addr must be
-// wavefront-uniform.  M0 carries the LDS base of the copy and is used by nothing else in these
-// kernels.
+// wavefront-uniform.  M0 carries the LDS base of the copy; the statements declare it clobbered, so
+// the compiler keeps nothing of its own in it across a copy.
 __device__ __forceinline__ void async_copy_b128(const void* gptr_lane, uint32_t lds_byte_addr) {
 #if defined(__HIP_DEVICE_COMPILE__)
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-               :: "s"(lds_byte_addr), "v"(gptr_lane) : "memory");
+               :: "s"(lds_byte_addr), "v"(gptr_lane) : "memory", "m0");
 #else
   (void)gptr_lane; (void)lds_byte_addr;
 #endif
@@ -46,7 +46,7 @@ __device__ __forceinline__ void async_copy_b128(const void* gbase_uniform, uint3
   const uint64_t base = (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)bits) |
                         ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(bits >> 32)) << 32);
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-               :: "s"(lds_byte_addr), "v"(byte_off_lane), "s"(base) : "memory");
+               :: "s"(lds_byte_addr), "v"(byte_off_lane), "s"(base) : "memory", "m0");
 #else
   (void)gbase_uniform; (void)byte_off_lane; (void)lds_byte_addr;
 #endif
@@ -54,7 +54,7 @@ __device__ __forceinline__ void async_copy_b128(const void* gbase_uniform, uint3
 __device__ __forceinline__ void async_copy_b32(const void* gptr_lane, uint32_t lds_byte_addr) {
 #if defined(__HIP_DEVICE_COMPILE__)
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off"
-               :: "s"(lds_byte_addr), "v"(gptr_lane) : "memory");
+               :: "s"(lds_byte_addr), "v"(gptr_lane) : "memory", "m0");
 #else
   (void)gptr_lane; (void)lds_byte_addr;
 #endif

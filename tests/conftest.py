@@ -30,7 +30,7 @@ def pytest_generate_tests(metafunc):
     # Which kernel a call takes depends on the problem (head dimension, length, number of heads):
     # the small problems of the parity tests would never reach some kernels.  Test modules that ask
     # for these fixtures run every test twice: with the library's own choice, and with the other
-    # kernel forced through the environment variables the launchers read on every call.
+    # kernel forced through the library's override hook.
     if "fwd_variant" in metafunc.fixturenames:
         metafunc.parametrize("fwd_variant", ["auto", "two_group"], indirect=True)
     if "dkv_variant" in metafunc.fixturenames:
@@ -38,18 +38,16 @@ def pytest_generate_tests(metafunc):
 
 
 @pytest.fixture
-def fwd_variant(request, monkeypatch):
-    if request.param == "two_group":
-        monkeypatch.setenv("ATTN_FWD_VARIANT", "pp")      # ignored at d = 32 and for block-sparse calls
-    else:
-        monkeypatch.delenv("ATTN_FWD_VARIANT", raising=False)
-    return request.param
+def fwd_variant(request):
+    from paper_2205_14135_amd import binding
+    binding.attn_debug_set_variant(fwd="pp" if request.param == "two_group" else "auto")   # ignored at d = 32 and for block-sparse calls
+    yield request.param
+    binding.attn_debug_set_variant(fwd="auto")
 
 
 @pytest.fixture
-def dkv_variant(request, monkeypatch):
-    if request.param == "role_split":
-        monkeypatch.setenv("ATTN_DKV_VARIANT", "rs")      # d = 128 takes that kernel anyway
-    else:
-        monkeypatch.delenv("ATTN_DKV_VARIANT", raising=False)
-    return request.param
+def dkv_variant(request):
+    from paper_2205_14135_amd import binding
+    binding.attn_debug_set_variant(dkv="rs" if request.param == "role_split" else "auto")   # d = 128 with dropout takes that kernel anyway
+    yield request.param
+    binding.attn_debug_set_variant(dkv="auto")

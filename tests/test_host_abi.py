@@ -33,6 +33,7 @@ def test_version_and_strerror(lib):
     texts = {binding.strerror(-i) for i in range(1, 10)}
     assert len(texts) == 9 and "unknown status" not in texts
     assert binding.strerror(-99) == "unknown status"
+    assert "16, 32, 64 or 128" in binding.strerror(-4)
 
 
 def _params(**kw):
@@ -100,6 +101,40 @@ def test_null_pointers_and_workspace(lib):
     assert lib.attn_blocksparse_bwd_workspace_bytes(ctypes.byref(_params(N=100))) == 0
     args_m = [v, 128, 0] + [v] * 9
     assert lib.attn_blocksparse_bwd(ctypes.byref(p), *args_m, v, need) == -7     # dense size is too small
+
+
+def test_tensor_alignment_and_overlapping_strides(lib):
+    p = _params()
+    v, odd = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1008)
+    for slot in range(4):   # Q, K, V, O: every tensor is accessed in 16-byte pieces
+        args = [v] * 5
+        args[slot] = odd
+        assert lib.attn_fwd(ctypes.byref(p), *args) == -2
+    need = lib.attn_bwd_workspace_bytes(ctypes.byref(p))
+    for slot in (0, 4, 6, 7, 8):   # Q, dO, dQ, dK, dV
+        args = [v] * 9
+        args[slot] = odd
+        assert lib.attn_bwd(ctypes.byref(p), *args, v, need) == -2
+    ok = lambda **kw: lib.attn_bwd_workspace_bytes(ctypes.byref(_params(**kw))) != 0
+    # head-major with padded rows, token-major view of [B,N,H,d], single-head / single-batch axes
+    assert ok(B=2, H=3, N=128, stride_b=3 * 128 * 72, stride_h=128 * 72, stride_n=72)
+    assert ok(B=2, H=3, N=128, stride_b=128 * 3 * 64, stride_h=64, stride_n=3 * 64)
+    assert ok(B=1, H=1, N=128, stride_b=0, stride_h=0, stride_n=64)
+    # aliasing layouts: a zero or too short stride on an axis of size > 1
+    assert not ok(B=2, H=1, N=128, stride_b=0, stride_h=128 * 64, stride_n=64)
+    assert not ok(B=1, H=2, N=128, stride_b=2 * 128 * 64, stride_h=0, stride_n=64)
+    assert not ok(B=1, H=2, N=128, stride_b=2 * 128 * 64, stride_h=64 * 64, stride_n=64)   # heads overlap by half
+    assert not ok(B=2, H=2, N=128, stride_b=128 * 64, stride_h=128 * 64, stride_n=64)      # batch 1 = head 1
+
+
+def test_variant_override_arguments(lib):
+    assert lib.attn_debug_set_variant(3, 0) == -2
+    assert lib.attn_debug_set_variant(0, -2) == -2
+    assert lib.attn_debug_set_variant(2, 1) == 0
+    assert lib.attn_debug_set_variant(-1, -1) == 0
+    assert lib.attn_debug_set_variant(0, 0) == 0
+    binding.attn_debug_set_variant(fwd="base", dkv="rs")
+    binding.attn_debug_set_variant(fwd="auto", dkv="auto")
 
 
 def test_mfma_rate_probe_arguments(lib):
