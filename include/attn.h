@@ -150,6 +150,24 @@ int attn_bwd(const attn_params* p, const void* Q, const void* K, const void* V,
              void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes);
 
 /*
+ * attn_bwd for callers that can neither allocate device memory nor pass a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments and results as attn_bwd (bit-identical), except that the two row vectors live in a
+ * fixed array inside the library, ATTN_STATIC_SCRATCH_BYTES per GPU, held from the first
+ * use on that GPU until the process ends.  The call allocates and frees nothing.  Problems whose
+ * attn_bwd_workspace_bytes(p) exceeds ATTN_STATIC_SCRATCH_BYTES (more than 2^20 query rows
+ * over all heads, counted in whole blocks of 128 per head) return ATTN_ERR_WORKSPACE.  All calls
+ * on one GPU share that GPU's array: calls that overlap in time on one GPU (different streams or
+ * threads) race and give wrong gradients; calls on one stream, or otherwise ordered, are safe,
+ * and no call reads what an earlier one left there.  The device that is current when the call
+ * is made must be the one that owns the tensors and the stream.
+ */
+#define ATTN_STATIC_SCRATCH_BYTES (8u << 20)
+int attn_bwd_static(const attn_params* p, const void* Q, const void* K, const void* V,
+                    const void* O, const void* dO, const float* LSE,
+                    void* dQ, void* dK, void* dV);
+
+/*
  * Block-sparse forward (Section 3.3, Algorithm 5): as attn_fwd, but entry
  * (i, j) is additionally masked out unless
  * block_mask[(i / mask_block) * T + (j / mask_block)] != 0, T = N / mask_block;

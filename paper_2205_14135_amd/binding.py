@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libattn_gfx950.so")
 ATTN_FP16, ATTN_BF16 = 0, 1
 
 SYMBOLS = (
-    "attn_fwd", "attn_bwd_workspace_bytes", "attn_blocksparse_bwd_workspace_bytes", "attn_bwd", "attn_blocksparse_fwd",
+    "attn_fwd", "attn_bwd_workspace_bytes", "attn_blocksparse_bwd_workspace_bytes", "attn_bwd", "attn_bwd_static", "attn_blocksparse_fwd",
     "attn_blocksparse_bwd", "attn_bwd_timed", "attn_debug_dropout_mask", "attn_debug_mfma_rate", "attn_debug_set_variant", "attn_strerror",
     "attn_version",
 )
@@ -68,6 +68,8 @@ def load() -> ctypes.CDLL:
     lib.attn_blocksparse_bwd_workspace_bytes.restype = sz
     lib.attn_bwd.argtypes = [P] + [vp] * 9 + [vp, sz]
     lib.attn_bwd.restype = ctypes.c_int
+    lib.attn_bwd_static.argtypes = [P] + [vp] * 9
+    lib.attn_bwd_static.restype = ctypes.c_int
     lib.attn_blocksparse_fwd.argtypes = [P, vp, i32, i64, vp, vp, vp, vp, vp]
     lib.attn_blocksparse_fwd.restype = ctypes.c_int
     lib.attn_blocksparse_bwd.argtypes = [P, vp, i32, i64] + [vp] * 9 + [vp, sz]
@@ -198,6 +200,20 @@ def attn_bwd(Q, K, V, O, dO, LSE, *, softmax_scale, causal=False, dropout_p=0.0,
     workspace, nbytes = _workspace(p, Q.device, workspace)
     _check(load().attn_bwd(ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE),
                            _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(workspace), nbytes), "attn_bwd")
+    return dQ, dK, dV
+
+
+STATIC_SCRATCH_BYTES = 8 << 20
+
+
+def attn_bwd_static(Q, K, V, O, dO, LSE, grads, *, softmax_scale, causal=False, dropout_p=0.0, seed=0,
+                    offset=0, o_fp32=False, stream=None, key_lengths=None):
+    """attn_bwd on the library's built-in scratch: the caller passes the outputs, nothing is allocated."""
+    _same_layout(Q, K, V, dO)
+    p = make_params(Q, softmax_scale, causal, dropout_p, seed, offset, o_fp32, stream, key_lengths)
+    dQ, dK, dV = grads
+    _check(load().attn_bwd_static(ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(LSE),
+                                  _ptr(dQ), _ptr(dK), _ptr(dV)), "attn_bwd_static")
     return dQ, dK, dV
 
 

@@ -7,6 +7,12 @@
 #include <cstdlib>
 #include <cmath>
 #include <cstring>
+#include <mutex>
+
+// Scratch of attn_bwd_static: every GPU that runs the library holds its own copy of this array, at
+// its own address, until the process ends.  In host code the name is only a handle for
+// hipGetSymbolAddress, never a device address.
+static __device__ __align__(256) unsigned char scratch[ATTN_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -170,6 +176,25 @@ int bwd_common(const attn_params* p, const uint8_t* mask, int64_t mask_sh, bool 
   return e == 0 ? ATTN_OK : ATTN_ERR_LAUNCH;
 }
 
+// Device address of the current GPU's copy of `scratch`: looked up once per device, with that
+// device current, and kept; nullptr if the runtime cannot tell.  Allocates nothing.
+void* static_scratch() {
+  constexpr int kMaxDevices = 64;
+  static std::atomic<void*> ptr[kMaxDevices];
+  static std::mutex mu;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  void* q = ptr[dev].load(std::memory_order_acquire);
+  if (q != nullptr) return q;
+  std::lock_guard<std::mutex> lock(mu);
+  q = ptr[dev].load(std::memory_order_relaxed);
+  if (q != nullptr) return q;
+  void* addr = nullptr;
+  if (hipGetSymbolAddress(&addr, HIP_SYMBOL(scratch)) != hipSuccess || addr == nullptr) return nullptr;
+  ptr[dev].store(addr, std::memory_order_release);
+  return addr;
+}
+
 // Kernel-choice overrides: set through attn_debug_set_variant; until then the values of
 // ATTN_FWD_VARIANT (base | pp) and ATTN_DKV_VARIANT (rs | fr), read once.
 std::atomic<int> g_fwd_variant{-1}, g_dkv_variant{-1};
@@ -226,6 +251,20 @@ int attn_bwd(const attn_params* p, const void* Q, const void* K, const void* V, 
              const void* dO, const float* LSE, void* dQ, void* dK, void* dV, void* workspace,
              size_t workspace_bytes) {
   return bwd_common(p, nullptr, 0, false, Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes);
+}
+
+int attn_bwd_static(const attn_params* p, const void* Q, const void* K, const void* V, const void* O,
+                    const void* dO, const float* LSE, void* dQ, void* dK, void* dV) {
+  Checked c;
+  const int st = check_params(p, &c);
+  if (st != ATTN_OK) return st;
+  if (ws_layout(p).d_bytes > (size_t)ATTN_STATIC_SCRATCH_BYTES) return ATTN_ERR_WORKSPACE;
+  if (!Q || !K || !V || !O || !dO || !LSE || !dQ || !dK || !dV) return ATTN_ERR_NULL;
+  void* ws = static_scratch();
+  if (ws == nullptr) return ATTN_ERR_LAUNCH;
+  // the two row vectors are written in full by the first launch before the second reads them:
+  // nothing of an earlier call's contents is ever read, nothing needs clearing
+  return bwd_common(p, nullptr, 0, false, Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ATTN_STATIC_SCRATCH_BYTES);
 }
 
 int attn_blocksparse_fwd(const attn_params* p, const uint8_t* block_mask, int32_t mask_block,
@@ -301,7 +340,7 @@ const char* attn_strerror(int status) {
     case ATTN_ERR_HEADDIM: return "head dimension must be 16, 32, 64 or 128";
     case ATTN_ERR_DROPOUT_P: return "dropout_p must be in [0, 1)";
     case ATTN_ERR_SCALE: return "softmax_scale must be finite and positive";
-    case ATTN_ERR_WORKSPACE: return "workspace is NULL, not 256-byte aligned, or too small";
+    case ATTN_ERR_WORKSPACE: return "workspace is NULL, not 256-byte aligned, or too small (attn_bwd_static: problem beyond the built-in scratch)";
     case ATTN_ERR_MASK: return "mask_block must be 128 and mask_stride_h 0 or >= T*T";
     case ATTN_ERR_LAUNCH: return "kernel launch failed";
     default: return "unknown status";

@@ -137,6 +137,19 @@ def test_variant_override_arguments(lib):
     binding.attn_debug_set_variant(fwd="auto", dkv="auto")
 
 
+def test_static_scratch_entry_point_rejects_large_problems(lib):
+    # 2^20 rows over all heads fill the built-in scratch exactly; one block more per head is refused
+    v = ctypes.c_void_p(0x1000)
+    big = _params(B=64, H=16, N=1024 + 128)
+    assert lib.attn_bwd_workspace_bytes(ctypes.byref(big)) > binding.STATIC_SCRATCH_BYTES
+    assert lib.attn_bwd_static(ctypes.byref(big), *([v] * 9)) == -7
+    assert "built-in scratch" in binding.strerror(-7)
+    fits = _params(B=64, H=16, N=1024)
+    assert lib.attn_bwd_workspace_bytes(ctypes.byref(fits)) == binding.STATIC_SCRATCH_BYTES
+    assert lib.attn_bwd_static(ctypes.byref(fits), *([v] * 8), ctypes.c_void_p(0)) == -1   # NULL dV: nothing launched
+    assert lib.attn_bwd_static(ctypes.byref(_params(d=7)), *([v] * 9)) == -4
+
+
 def test_mfma_rate_probe_arguments(lib):
     v, z = ctypes.c_void_p(0x1000), ctypes.c_void_p(0)
     assert lib.attn_debug_mfma_rate(binding.ATTN_BF16, 10, z, z, None) == -1
