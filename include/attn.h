@@ -49,7 +49,7 @@
  * number of heads; every choice computes the same operation to the same
  * tolerance.  attn_debug_set_variant overrides the choice for comparisons and
  * tests; its initial values come from two environment variables read once, when
- * the first call needs them: ATTN_FWD_VARIANT=base|pp and ATTN_DKV_VARIANT=rs|fr.
+ * the first call needs them: ATTN_FWD_VARIANT=base|pp and ATTN_DKV_VARIANT=rs|fr|w64.
  * Unset, the library picks by measurement.
  */
 #ifndef ATTN_H_
@@ -230,7 +230,8 @@ int attn_debug_mfma_rate(int32_t dtype, int32_t iters, float* sink, void* stream
  * Test and comparison hook, outside the paper's operation: which kernel serves the calls that
  * have a choice.  fwd_variant: 0 = by measurement, 1 = free-running forward kernel, 2 = two-group
  * forward kernel (where both exist).  dkv_variant: 0 = by measurement, 1 = role-split dK/dV kernel
- * wherever it exists, 2 = one-wavefront dK/dV kernels only (never the 64-keys-per-wavefront one).
+ * wherever it exists, 2 = one-wavefront dK/dV kernels with 32 keys per wavefront only, 3 = the
+ * 64-keys-per-wavefront dK/dV kernel wherever it exists (d = 128, no dropout, N >= 512, N % 32 == 0).
  * -1 leaves a setting unchanged.  Process-wide and thread-safe; affects calls issued afterwards.
  */
 int attn_debug_set_variant(int32_t fwd_variant, int32_t dkv_variant);

@@ -294,7 +294,7 @@ def attn_debug_mfma_rate(dtype: str, iters: int, sink: torch.Tensor) -> float:
 
 
 FWD_VARIANTS = {"auto": 0, "base": 1, "pp": 2}
-DKV_VARIANTS = {"auto": 0, "rs": 1, "fr": 2}
+DKV_VARIANTS = {"auto": 0, "rs": 1, "fr": 2, "w64": 3}
 
 
 def attn_debug_set_variant(fwd: Optional[str] = None, dkv: Optional[str] = None) -> None:

@@ -196,12 +196,12 @@ void* static_scratch() {
 }
 
 // Kernel-choice overrides: set through attn_debug_set_variant; until then the values of
-// ATTN_FWD_VARIANT (base | pp) and ATTN_DKV_VARIANT (rs | fr), read once.
+// ATTN_FWD_VARIANT (base | pp) and ATTN_DKV_VARIANT (rs | fr | w64), read once.
 std::atomic<int> g_fwd_variant{-1}, g_dkv_variant{-1};
-int env_choice(const char* name, char c1, char c2) {
+int env_choice(const char* name, char c1, char c2, char c3 = 0) {
   const char* v = std::getenv(name);
   if (v == nullptr) return 0;
-  return v[0] == c1 ? 1 : (v[0] == c2 ? 2 : 0);
+  return v[0] == c1 ? 1 : (v[0] == c2 ? 2 : (c3 != 0 && v[0] == c3 ? 3 : 0));
 }
 
 }  // namespace
@@ -219,7 +219,7 @@ int fwd_variant() {
 int dkv_variant() {
   int v = g_dkv_variant.load(std::memory_order_relaxed);
   if (v < 0) {
-    v = env_choice("ATTN_DKV_VARIANT", 'r', 'f');
+    v = env_choice("ATTN_DKV_VARIANT", 'r', 'f', 'w');
     int expected = -1;
     if (!g_dkv_variant.compare_exchange_strong(expected, v)) v = expected;
   }
@@ -325,7 +325,7 @@ int attn_debug_mfma_rate(int32_t dtype, int32_t iters, float* sink, void* stream
 }
 
 int attn_debug_set_variant(int32_t fwd_variant, int32_t dkv_variant) {
-  if (fwd_variant < -1 || fwd_variant > 2 || dkv_variant < -1 || dkv_variant > 2) return ATTN_ERR_SHAPE;
+  if (fwd_variant < -1 || fwd_variant > 2 || dkv_variant < -1 || dkv_variant > 3) return ATTN_ERR_SHAPE;
   if (fwd_variant >= 0) g_fwd_variant.store(fwd_variant);
   if (dkv_variant >= 0) g_dkv_variant.store(dkv_variant);
   return ATTN_OK;

@@ -510,7 +510,14 @@ int launch_dkv_rs(const KArgs& a, int dtype, int d, bool causal, bool dropout, b
   // (head dimension 16 exists in that kernel only)
   if (!sparse && d <= 64 && (!force_role_split() || a.dvalid < d)) return launch_dkv_fr(a, dtype, d, causal, dropout, false, 0, s);
   // d = 128, dense, no dropout: the one-wavefront kernel with the V block in LDS (attn_bwd_dkv_fr128.hip)
-  if (!sparse && d == 128 && !dropout && !force_role_split()) return launch_dkv_fr128(a, dtype, causal, s);
+  // (with 64 keys per wavefront where a head has at least two blocks of 256 keys and whole 32-query tiles: attn_bwd_dkv_w64.hip)
+  if (!sparse && d == 128 && !dropout && !force_role_split()) {
+    // measured against the 32-key kernel: 1 % faster at N = 2048, 5 % at 4096, 7 % at 16384; slower below,
+    // and slower under the causal mask at every length (its 256-key work items balance worse)
+    const bool w64 = dkv_variant() == 3 || (dkv_variant() == 0 && !causal && a.N >= 2048);
+    if (w64 && a.N >= 512 && a.N % 32 == 0) return launch_dkv_w64(a, dtype, causal, s);
+    return launch_dkv_fr128(a, dtype, causal, s);
+  }
   if (dtype == 0 && d == 32) return launch_td<_Float16, 32>(a, causal, dropout, sparse, s);
   if (dtype == 1 && d == 32) return launch_td<__bf16, 32>(a, causal, dropout, sparse, s);
   if (dtype == 0 && d == 64) return launch_td<_Float16, 64>(a, causal, dropout, sparse, s);

@@ -57,7 +57,8 @@ enum { kHeavyBlocks = 24, kSegBlocks = 12, kMaxSegs = 32, kSegHeader = 8, kCompu
 
 // Kernel-choice overrides (attn_debug_set_variant; initial values from the environment, read once
 // when first needed).  fwd: 0 = by measurement, 1 = free-running kernel, 2 = two-group kernel;
-// dkv: 0 = by measurement, 1 = role-split kernel wherever it exists, 2 = the 64-key kernel is not used.
+// dkv: 0 = by measurement, 1 = role-split kernel wherever it exists, 2 = the 64-key kernel is not used,
+// 3 = the 64-key kernel wherever it exists.
 int fwd_variant();
 int dkv_variant();
 
@@ -74,6 +75,8 @@ int launch_dkv_fr(const KArgs& a, int dtype, int d, bool causal, bool dropout, b
                   hipStream_t s);
 // the same at d = 128 for dense problems without causal mask and dropout (attn_bwd_dkv_fr128.hip)
 int launch_dkv_fr128(const KArgs& a, int dtype, bool causal, hipStream_t s);
+// the same with 64 keys per wavefront and the accumulators in the accumulation registers (attn_bwd_dkv_w64.hip)
+int launch_dkv_w64(const KArgs& a, int dtype, bool causal, hipStream_t s);
 // dense forward with two wavefront groups in ping-pong (attn_fwd_pp.hip); sets its own work items
 int launch_fwd_pp(const KArgs& a, int dtype, int d, bool causal, bool dropout, hipStream_t s);
 // MFMA-only kernel for measuring the sustained matrix rate (attn_probe.hip); *flops = FLOPs launched

@@ -114,6 +114,11 @@ template <typename T, int D, int NW, int ROWS = 64> struct TileAsync {
     for (int p = 0; p < PER_WAVE; ++p)
       if (!skip(p)) async_copy_b128(g_row0, goff[p], base + p * 1024);
   }
+  // copy number p (0 .. PER_WAVE - 1) of this wavefront alone, for callers that spread a tile's copies out
+  __device__ __forceinline__ void copy_one(const T* g_row0, const T* lds_tile, int p) const {
+    const uint32_t base = __builtin_amdgcn_readfirstlane(lds_addr(lds_tile) + (wave * PER_WAVE) * 1024);
+    if (!skip(p)) async_copy_b128(g_row0, goff[p], base + p * 1024);
+  }
   // The last tile of a tensor whose row count is not a multiple of 64: only rows_valid (>= 1) rows
   // exist; the LDS rows beyond them receive a copy of the last valid row (finite values that the
   // kernels mask), so that nothing outside the tensor is read.

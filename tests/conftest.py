@@ -34,7 +34,7 @@ def pytest_generate_tests(metafunc):
     if "fwd_variant" in metafunc.fixturenames:
         metafunc.parametrize("fwd_variant", ["auto", "two_group"], indirect=True)
     if "dkv_variant" in metafunc.fixturenames:
-        metafunc.parametrize("dkv_variant", ["auto", "role_split"], indirect=True)
+        metafunc.parametrize("dkv_variant", ["auto", "role_split", "one_wave_32_keys", "one_wave_64_keys"], indirect=True)
 
 
 @pytest.fixture
@@ -48,6 +48,9 @@ def fwd_variant(request):
 @pytest.fixture
 def dkv_variant(request):
     from paper_2205_14135_amd import binding
-    binding.attn_debug_set_variant(dkv="rs" if request.param == "role_split" else "auto")   # d = 128 with dropout takes that kernel anyway
+    # (d = 128 with dropout takes the role-split kernel anyway; "fr" keeps the 64-keys-per-wavefront
+    # kernel of d = 128 out and "w64" brings it in wherever it exists, so that both one-wavefront
+    # kernels are reached at every length and under the causal mask)
+    binding.attn_debug_set_variant(dkv={"role_split": "rs", "one_wave_32_keys": "fr", "one_wave_64_keys": "w64"}.get(request.param, "auto"))
     yield request.param
     binding.attn_debug_set_variant(dkv="auto")

@@ -78,3 +78,25 @@ def test_causal_paired_blocks_odd_count(N, d):
     res = hp.check_backward(t, dev, "bf16", 1 / math.sqrt(d), causal=True)
     print("causal pairs bwd", N, d, res)
     hp.assert_backward_ok(res)
+
+
+@pytest.mark.parametrize("N,causal,dtype", [(768, False, "bf16"), (1120, False, "fp16"), (1120, True, "bf16"),
+                                            (2048, False, "bf16"), (544, True, "fp16")])
+def test_d128_blocks_of_256_keys(N, causal, dtype):
+    """Lengths that are whole 32-query tiles (the 64-keys-per-wavefront dK/dV kernel takes them when it
+    is chosen or forced): whole and ragged 256-key blocks, tile counts that are and are not multiples
+    of the three-buffer ring, the causal diagonal inside a wavefront's 64 keys."""
+    t, dev = hp.make_case(1, 2, N, 128, dtype, 4100 + N + causal)
+    res = hp.check_backward(t, dev, dtype, 1 / math.sqrt(128), causal=causal)
+    print("256-key blocks bwd", N, causal, dtype, res)
+    hp.assert_backward_ok(res)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_d128_blocks_of_256_keys_with_key_padding(causal):
+    """Key padding on top: padded keys inside a wavefront's 64 keys, a key block that is all padding,
+    an empty sequence."""
+    t, dev = hp.make_case(4, 1, 1024, 128, "bf16", 4300 + causal)
+    res = hp.check_backward(t, dev, "bf16", 1 / math.sqrt(128), causal=causal, key_lengths=[1024, 700, 130, 0])
+    print("256-key blocks bwd, key padding", causal, res)
+    hp.assert_backward_ok(res)

@@ -129,6 +129,7 @@ def test_tensor_alignment_and_overlapping_strides(lib):
 
 def test_variant_override_arguments(lib):
     assert lib.attn_debug_set_variant(3, 0) == -2
+    assert lib.attn_debug_set_variant(0, 4) == -2
     assert lib.attn_debug_set_variant(0, -2) == -2
     assert lib.attn_debug_set_variant(2, 1) == 0
     assert lib.attn_debug_set_variant(-1, -1) == 0
