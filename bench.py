@@ -144,17 +144,26 @@ def run_gpu(cfg, steps, warmup, seed, mask_override=None, nsets=1):
         else:
             binding.attn_blocksparse_fwd(g["Q"], g["K"], g["V"], bm, out=z["O"], lse=z["L"], **kw)
 
-    def bwd(z, events):
+    def bwd(z):      # the product call
+        g = z["g"]
+        if bm is None:
+            binding.attn_bwd(g["Q"], g["K"], g["V"], z["O"], g["dO"], z["L"], grads=z["grads"], workspace=ws, **kw)
+        else:
+            binding.attn_blocksparse_bwd(g["Q"], g["K"], g["V"], z["O"], g["dO"], z["L"], bm, grads=z["grads"],
+                                         workspace=ws, **kw)
+
+    def bwd_timed(z, events):      # the same launches with events between them, for the per-kernel figures
         g = z["g"]
         binding.attn_bwd_timed(g["Q"], g["K"], g["V"], z["O"], g["dO"], z["L"], events, block_mask=bm,
                                grads=z["grads"], workspace=ws, **kw)
 
-    scratch_ev = [hev.new() for _ in range(4)]
     for i in range(max(warmup, nsets)):     # every set needs its O and row statistic before a backward
         fwd(sets[i % nsets])
-        bwd(sets[i % nsets], scratch_ev)
+        bwd(sets[i % nsets])
     torch.cuda.synchronize()
-    evs = [[hev.new() for _ in range(5)] for _ in range(steps)]   # f0, f1=b0, b1, b2, b3
+    # ---- the timed region: `steps` forward + backward passes through attn_fwd / attn_bwd; the only
+    # extra work on the stream is one event record before and after each pass
+    evs = [[hev.new() for _ in range(3)] for _ in range(steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(steps):
@@ -162,60 +171,55 @@ def run_gpu(cfg, steps, warmup, seed, mask_override=None, nsets=1):
         z = sets[s % nsets]
         hev.record(e[0], stream)
         fwd(z)
-        bwd(z, e[1:5])
+        hev.record(e[1], stream)
+        bwd(z)
+        hev.record(e[2], stream)
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
-    # event intervals, labelled with the kernels the library launches for this workload (the forward
-    # choice mirrors launch_fwd() in csrc/attn_fwd.hip)
-    if cfg["sparse"]:
-        use_pp = False
-    else:
-        n_qt = (N + 255) // 256
-        pp_items = B * H * ((n_qt + 1) // 2 if cfg["causal"] else n_qt)
-        use_pp = (d == 128 and pp_items >= 256 and
-                  (cfg["causal"] if cfg["p"] > 0 else (N >= 1024 or (cfg["causal"] and N >= 512))))
-    # dK/dV: the one-wavefront kernels at d <= 64 and (dense, no dropout) at d = 128, else the
-    # role-split one (launch_dkv_rs())
-    if d <= 64:
-        dkv = "dkv_fr_kernel"
-    elif not cfg["sparse"] and cfg["p"] == 0:
-        dkv = "dkv_fr128_kernel"
-    else:
-        dkv = "dkv_rs_kernel"
-    names = ["fwd_pp_kernel" if use_pp else "fwd_kernel", "dq_kernel", dkv]
+    fwd_steps = np.array([hev.elapsed_ms(e[0], e[1]) for e in evs])
+    bwd_steps = np.array([hev.elapsed_ms(e[1], e[2]) for e in evs])
+    stats = dict(fwd_mean=float(fwd_steps.mean()), fwd_median=float(np.median(fwd_steps)), fwd_min=float(fwd_steps.min()),
+                 bwd_mean=float(bwd_steps.mean()), bwd_median=float(np.median(bwd_steps)), bwd_min=float(bwd_steps.min()))
+    # ---- a second pass for the per-kernel durations (attn_bwd_timed records events between the
+    # launches of the backward pass); the kernels are named by the library's own choice
+    pk = binding.make_params(g0["Q"], tau, cfg["causal"], cfg["p"], inputs.BASE_DROPOUT_SEED, 0)
+    n_fwd, n_dkv = binding.attn_debug_kernel_choice(pk, cfg["sparse"])
+    names = [n_fwd, "dq_kernel", n_dkv]
+    kevs = [[hev.new() for _ in range(5)] for _ in range(steps)]   # f0, f1=b0, b1, b2, b3
+    for s in range(steps):
+        e = kevs[s]
+        z = sets[s % nsets]
+        hev.record(e[0], stream)
+        fwd(z)
+        bwd_timed(z, e[1:5])
+    torch.cuda.synchronize()
     # events: e[0] before the forward, e[1] = e[2] before the backward, e[3] after dQ, e[4] after dK/dV
     spans = [(0, 1), (1, 3), (3, 4)]
-    per_step = {n: [] for n in names}
-    for e in evs:
-        for (i0, i1), n in zip(spans, names):
-            per_step[n].append(hev.elapsed_ms(e[i0], e[i1]))
-    dur = {n: sum(v) / steps for n, v in per_step.items()}
-    fwd_steps = np.array(per_step[names[0]])
-    bwd_steps = np.sum([per_step[n] for n in names[1:]], axis=0)
-    stats = dict(fwd_median=float(np.median(fwd_steps)), fwd_min=float(fwd_steps.min()),
-                 bwd_median=float(np.median(bwd_steps)), bwd_min=float(bwd_steps.min()))
+    dur = {n: sum(hev.elapsed_ms(e[i0], e[i1]) for e in kevs) / steps for (i0, i1), n in zip(spans, names)}
     hev.close()
     peak_bytes = torch.cuda.max_memory_allocated(dev)
     return dict(ms_per_step=wall_ms / steps, kernel_ms=dur, names=names, nnz=nnz, tensors=t, block_mask=bm_np, tau=tau,
                 peak_bytes=peak_bytes, stats=stats)
 
 
-def measured_mfma_rate(dtype):
+def measured_mfma_rate(dtype, operand_sets=1):
     """TFLOP/s of a kernel that only issues matrix instructions on register operands: what this
-    GPU sustains at the clock it holds under that load (the published peak assumes 2.4 GHz)."""
+    GPU sustains at the clock it holds under that load (the published peak assumes 2.4 GHz).
+    operand_sets = 1: the same two registers every time; 4: four pseudo-random operand pairs in
+    turn (more bits change per instruction, the clock the GPU holds is lower)."""
     import torch
     from paper_2205_14135_amd import binding
     dev = torch.device("cuda:0")
     sink = torch.zeros(64, dtype=torch.float32, device=dev)
     stream = torch.cuda.current_stream(dev).cuda_stream
     hev = HipEvents()
-    binding.attn_debug_mfma_rate(dtype, 2000, sink)
+    binding.attn_debug_mfma_rate(dtype, 2000, sink, operand_sets)
     torch.cuda.synchronize()
     e = [hev.new() for _ in range(4)]
     flops = 0.0
     for i in range(3):
         hev.record(e[i], stream)
-        flops = binding.attn_debug_mfma_rate(dtype, 20000, sink)
+        flops = binding.attn_debug_mfma_rate(dtype, 20000, sink, operand_sets)
     hev.record(e[3], stream)
     torch.cuda.synchronize()
     ms = hev.elapsed_ms(e[0], e[3]) / 3
@@ -376,7 +380,9 @@ def cpu_baseline(cfg, run, budget_s=12.0, max_s=30.0):
 
 
 def load_traffic(workload, kernel):
-    """HBM bytes per launch from committed rocprofv3 counter runs, if recorded for this workload."""
+    """HBM bytes per launch of this kernel on this workload from the committed rocprofv3 counter
+    runs (profiles/hbm_traffic.json, written from the FETCH_SIZE / WRITE_SIZE runs whose summary is
+    profiles/<workload>_hbm_counters.txt): None unless that kernel was recorded for that workload."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if not os.path.exists(path):
         return None
@@ -386,6 +392,15 @@ def load_traffic(workload, kernel):
         return tab.get(workload, {}).get(kernel)
     except Exception:
         return None
+
+
+def kernel_bytes(cfg):
+    """Minimum HBM bytes per launch of the three kernels: forward reads Q, K, V and writes O and the
+    row statistic; the dQ kernel reads Q, K, V, O, dO and the statistic and writes dQ and the two row
+    vectors; the dK/dV kernel reads Q, K, V, dO and the row vectors and writes dK, dV."""
+    rows = cfg["B"] * cfg["H"] * cfg["N"]
+    elem = rows * cfg["d"] * 2
+    return [4 * elem + 4 * rows, 6 * elem + 12 * rows, 6 * elem + 8 * rows]
 
 
 def main():
@@ -484,15 +499,41 @@ def main():
     rot = run_gpu(cfg, args.steps, args.warmup, inputs.BASE_SEED + 3, nsets=ROTATING_SETS)
     rot_ms = rot["ms_per_step"]
     del rot
-    mfma_rate = measured_mfma_rate(cfg["dtype"])
+    mfma_rate = measured_mfma_rate(cfg["dtype"], 1)
+    mfma_rate_varied = measured_mfma_rate(cfg["dtype"], 4)
     kms = run["kernel_ms"]
-    # algorithmic FLOPs of each launch: forward two tile products; dK/dV kernel four of the five
-    # backward products (S, dP, dV, dK); dQ kernel one (its S and dP are recomputation)
-    n_fwd, n_dq, n_dkv = run["names"]
-    algo = {n_fwd: f_fwd, n_dq: 0.5 * f_fwd, n_dkv: 2.0 * f_fwd}
-    dominant = max(algo, key=lambda n: kms[n])
-    achieved = algo[dominant] / kms[dominant] * 1e-9
+    st = run["stats"]
     peak = PEAK_TFLOPS[cfg["dtype"]]
+    # Tile products per launch (Algorithm 4 has five in the backward pass; one tile product over the
+    # whole problem is 2 B H N^2 d FLOPs = f_fwd / 2).  Algorithmic: forward S, PV; dK/dV kernel
+    # S, dP, dV, dK; dQ kernel dQ.  Executed: the dQ kernel recomputes S and dP as well.
+    n_fwd, n_dq, n_dkv = run["names"]
+    products = {n_fwd: (2, 2), n_dq: (1, 3), n_dkv: (4, 4)}
+    algo = {n: products[n][0] * 0.5 * f_fwd for n in run["names"]}
+    executed = {n: products[n][1] * 0.5 * f_fwd for n in run["names"]}
+    kbytes = dict(zip(run["names"], kernel_bytes(cfg)))
+    dominant = max(kms, key=lambda n: kms[n])
+    # which roofline bounds the dominant kernel: the longer of its algorithmic FLOPs at the matrix
+    # peak and its minimum bytes at the HBM peak
+    t_mfma = algo[dominant] / (peak * 1e9)            # ms
+    t_hbm = kbytes[dominant] / (PEAK_HBM_GBPS * 1e6)  # ms
+    if t_mfma >= t_hbm:
+        roof = {"bound": "mfma", "kernel": dominant, "achieved": round(algo[dominant] / kms[dominant] * 1e-9, 2),
+                "peak": peak, "unit": "TFLOP/s", "frac": round(algo[dominant] / kms[dominant] * 1e-9 / peak, 4)}
+    else:
+        gbps = kbytes[dominant] / kms[dominant] * 1e-6
+        roof = {"bound": "hbm", "kernel": dominant, "achieved": round(gbps, 1), "peak": PEAK_HBM_GBPS,
+                "unit": "GB/s", "frac": round(gbps / PEAK_HBM_GBPS, 4)}
+    roof["traffic"] = load_traffic(args.workload, dominant)
+    roof["traffic_source"] = ("profiles/hbm_traffic.json (rocprofv3 FETCH_SIZE + WRITE_SIZE per launch of this kernel "
+                              "on this workload)" if roof["traffic"] is not None else None)
+    roof["algorithmic_bytes"] = kbytes[dominant]
+    roof["avg_ms"] = round(kms[dominant], 4)
+    f_bwd = 2.5 * f_fwd
+    passes = {
+        "fwd": {"ms": round(st["fwd_mean"], 4), "tflops": round(f_fwd / st["fwd_mean"] * 1e-9, 1)},
+        "bwd": {"ms": round(st["bwd_mean"], 4), "tflops": round(f_bwd / st["bwd_mean"] * 1e-9, 1)},
+    }
     out = {
         "metric": "attention fwd+bwd TFLOP/s",
         "value": round(value, 2),
@@ -508,21 +549,32 @@ def main():
         "data": "synthetic",
         "config": {"workload": args.workload, **{k: cfg[k] for k in ("B", "H", "N", "d", "causal", "p", "sparse")}},
         "frac_of_mfma_peak": round(value / peak, 4),
+        # whole passes against the published matrix peak, FLOPs as the metric counts them (forward
+        # 4 B H N^2 d, backward 2.5 x), timed through attn_fwd / attn_bwd inside the timed region
+        "fwd_frac": round(f_fwd / st["fwd_mean"] * 1e-9 / peak, 4),
+        "bwd_frac": round(f_bwd / st["bwd_mean"] * 1e-9 / peak, 4),
+        "step_frac": round(value / peak, 4),
+        "passes": passes,
         "cache": "one set of tensors, reused every step (the value above)",
         "rotating_buffers": {"sets": ROTATING_SETS, "ms_per_step": round(rot_ms, 4),
                              "value": round(total / rot_ms * 1e-9, 2)},
-        "measured_mfma_rate": {"tflops": round(mfma_rate, 1), "frac_of_it": round(value / mfma_rate, 4),
-                               "what": "register-operand 32x32x16 MFMA loop on this GPU, same dtype"},
-        "step_stats_ms": {k: round(v, 4) for k, v in run["stats"].items()},
-        "roofline": {
-            "bound": "mfma", "kernel": dominant, "achieved": round(achieved, 2), "peak": peak,
-            "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
-            "traffic": load_traffic(args.workload, dominant),
-            "avg_ms": round(kms[dominant], 4),
-        },
+        "measured_mfma_rate": {
+            "tflops": round(mfma_rate, 1), "frac_of_it": round(value / mfma_rate, 4),
+            "what": "register-operand 32x32x16 MFMA loop on this GPU, same dtype, the same two operand registers every time",
+            "varied_operands_tflops": round(mfma_rate_varied, 1),
+            "frac_of_varied": round(value / mfma_rate_varied, 4),
+            "varied_what": "the same loop over four pseudo-random operand pairs in turn: the clock this GPU holds "
+                           "when operand bits change as in a real product"},
+        "step_stats_ms": {k: round(v, 4) for k, v in st.items()},
+        "roofline": roof,
         "kernels": {n: {"avg_ms": round(v, 4),
-                        "algorithmic_tflops": (round(algo[n] / v * 1e-9, 1) if n in algo else None)}
+                        "tile_products_algorithmic": products[n][0], "tile_products_executed": products[n][1],
+                        "algorithmic_tflops": round(algo[n] / v * 1e-9, 1),
+                        "executed_tflops": round(executed[n] / v * 1e-9, 1),
+                        "executed_frac_of_peak": round(executed[n] / v * 1e-9 / peak, 4)}
                     for n, v in kms.items()},
+        "kernels_note": "per-kernel durations from a second pass of the same steps through attn_bwd_timed "
+                        "(events between the launches); backward: 5 tile products counted, 7 executed",
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, run)

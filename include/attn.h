@@ -220,11 +220,26 @@ int attn_debug_dropout_mask(const attn_params* p, uint8_t* keep);
  * only issues 32x32x16 matrix instructions of the given dtype on register operands
  * (2048 workgroups of 4 wavefronts, 4 * iters instructions per wavefront), so a
  * benchmark that times the launch can quote the matrix rate this GPU sustains under
- * load next to the published peak.  sink: device pointer to at least one float, never
- * written in practice; *flops (host pointer, may be NULL) receives the number of
- * floating-point operations launched.  iters in [1, 2^20].  Asynchronous.
+ * load next to the published peak.  operand_sets = 1: every instruction reads the same
+ * two registers (fewest bits change between instructions: the highest clock the GPU
+ * holds); operand_sets = 4: consecutive instructions read four different pseudo-random
+ * operand pairs in turn, as the tile products of a real kernel do.  sink: device pointer
+ * to at least one float, never written in practice; *flops (host pointer, may be NULL)
+ * receives the number of floating-point operations launched.  iters in [1, 2^20].
+ * Asynchronous.
  */
-int attn_debug_mfma_rate(int32_t dtype, int32_t iters, float* sink, void* stream, double* flops);
+int attn_debug_mfma_rate(int32_t dtype, int32_t iters, int32_t operand_sets, float* sink, void* stream,
+                         double* flops);
+
+/*
+ * Measurement aid: which kernels attn_fwd / attn_bwd (sparse = 0) or the block-sparse
+ * entry points (sparse != 0) would launch for these params, without launching anything.
+ * *fwd_kernel: 0 = free-running forward kernel, 1 = two-group forward kernel.
+ * *dkv_kernel: 0 = role-split dK/dV kernel, 1 = one-wavefront kernel (d <= 64),
+ * 2 = one-wavefront kernel for d = 128 (32 keys per wavefront), 3 = the same with 64 keys
+ * per wavefront.  (The dQ kernel is the same for every problem.)
+ */
+int attn_debug_kernel_choice(const attn_params* p, int32_t sparse, int32_t* fwd_kernel, int32_t* dkv_kernel);
 
 /*
  * Test and comparison hook, outside the paper's operation: which kernel serves the calls that

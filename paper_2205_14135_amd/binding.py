@@ -19,7 +19,7 @@ ATTN_FP16, ATTN_BF16 = 0, 1
 
 SYMBOLS = (
     "attn_fwd", "attn_bwd_workspace_bytes", "attn_blocksparse_bwd_workspace_bytes", "attn_bwd", "attn_bwd_static", "attn_blocksparse_fwd",
-    "attn_blocksparse_bwd", "attn_bwd_timed", "attn_debug_dropout_mask", "attn_debug_mfma_rate", "attn_debug_set_variant", "attn_strerror",
+    "attn_blocksparse_bwd", "attn_bwd_timed", "attn_debug_dropout_mask", "attn_debug_mfma_rate", "attn_debug_kernel_choice", "attn_debug_set_variant", "attn_strerror",
     "attn_version",
 )
 
@@ -78,7 +78,9 @@ def load() -> ctypes.CDLL:
     lib.attn_bwd_timed.restype = ctypes.c_int
     lib.attn_debug_dropout_mask.argtypes = [P, vp]
     lib.attn_debug_dropout_mask.restype = ctypes.c_int
-    lib.attn_debug_mfma_rate.argtypes = [i32, i32, vp, vp, ctypes.POINTER(ctypes.c_double)]
+    lib.attn_debug_mfma_rate.argtypes = [i32, i32, i32, vp, vp, ctypes.POINTER(ctypes.c_double)]
+    lib.attn_debug_kernel_choice.argtypes = [P, i32, ctypes.POINTER(i32), ctypes.POINTER(i32)]
+    lib.attn_debug_kernel_choice.restype = ctypes.c_int
     lib.attn_debug_mfma_rate.restype = ctypes.c_int
     lib.attn_debug_set_variant.argtypes = [i32, i32]
     lib.attn_debug_set_variant.restype = ctypes.c_int
@@ -283,12 +285,24 @@ def attn_debug_dropout_mask(B, H, N, dropout_p, seed, offset, device="cuda") -> 
     return keep
 
 
-def attn_debug_mfma_rate(dtype: str, iters: int, sink: torch.Tensor) -> float:
+FWD_KERNELS = ("fwd_kernel", "fwd_pp_kernel")
+DKV_KERNELS = ("dkv_rs_kernel", "dkv_fr_kernel", "dkv_fr128_kernel", "dkv_w64_kernel")
+
+
+def attn_debug_kernel_choice(p: AttnParams, sparse: bool = False) -> Tuple[str, str]:
+    """Names of the forward and dK/dV kernels the library would launch for these params."""
+    f, k = ctypes.c_int32(), ctypes.c_int32()
+    _check(load().attn_debug_kernel_choice(ctypes.byref(p), int(bool(sparse)), ctypes.byref(f), ctypes.byref(k)),
+           "attn_debug_kernel_choice")
+    return FWD_KERNELS[f.value], DKV_KERNELS[k.value]
+
+
+def attn_debug_mfma_rate(dtype: str, iters: int, sink: torch.Tensor, operand_sets: int = 1) -> float:
     """Launches the matrix-instruction-only kernel on the current stream; returns the FLOPs launched."""
     fl = ctypes.c_double()
     code = {"fp16": 0, "bf16": 1}[dtype]
     stream = ctypes.c_void_p(int(torch.cuda.current_stream(sink.device).cuda_stream))
-    _check(load().attn_debug_mfma_rate(code, int(iters), _ptr(sink), stream, ctypes.byref(fl)),
+    _check(load().attn_debug_mfma_rate(code, int(iters), int(operand_sets), _ptr(sink), stream, ctypes.byref(fl)),
            "attn_debug_mfma_rate")
     return float(fl.value)
 

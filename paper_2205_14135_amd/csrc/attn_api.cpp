@@ -316,12 +316,25 @@ int attn_debug_dropout_mask(const attn_params* p, uint8_t* keep) {
   return e == 0 ? ATTN_OK : ATTN_ERR_LAUNCH;
 }
 
-int attn_debug_mfma_rate(int32_t dtype, int32_t iters, float* sink, void* stream, double* flops) {
+int attn_debug_mfma_rate(int32_t dtype, int32_t iters, int32_t operand_sets, float* sink, void* stream,
+                         double* flops) {
   if (sink == nullptr) return ATTN_ERR_NULL;
   if (dtype != ATTN_FP16 && dtype != ATTN_BF16) return ATTN_ERR_DTYPE;
   if (iters < 1 || iters > (1 << 20)) return ATTN_ERR_SHAPE;
-  const int e = attn::launch_mfma_rate(dtype, iters, sink, (hipStream_t)stream, flops);
+  if (operand_sets != 1 && operand_sets != 4) return ATTN_ERR_SHAPE;
+  const int e = attn::launch_mfma_rate(dtype, iters, operand_sets, sink, (hipStream_t)stream, flops);
   return e == 0 ? ATTN_OK : ATTN_ERR_LAUNCH;
+}
+
+int attn_debug_kernel_choice(const attn_params* p, int32_t sparse, int32_t* fwd_kernel, int32_t* dkv_kernel) {
+  Checked c;
+  const int st = check_params(p, &c);
+  if (st != ATTN_OK) return st;
+  if (fwd_kernel == nullptr || dkv_kernel == nullptr) return ATTN_ERR_NULL;
+  if (sparse != 0 && p->N % attn::kMaskBlock != 0) return ATTN_ERR_SHAPE;
+  *fwd_kernel = attn::choose_fwd(c.k, c.d, c.causal, c.dropout, sparse != 0);
+  *dkv_kernel = attn::choose_dkv(c.k, c.d, c.causal, c.dropout, sparse != 0);
+  return ATTN_OK;
 }
 
 int attn_debug_set_variant(int32_t fwd_variant, int32_t dkv_variant) {

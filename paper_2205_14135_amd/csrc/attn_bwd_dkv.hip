@@ -469,7 +469,7 @@ int launch_td(KArgs a, bool causal, bool dropout, bool sparse, hipStream_t s) {
     a.n_items = a.B * a.H * ((a.T + 1) / 2);
     a.chunk = (a.n_items + kXcds - 1) / kXcds;
   }
-  if (sparse && D <= 64 && (!force_role_split() || a.dvalid < D)) {
+  if (sparse && choose_dkv(a, D, causal, dropout, sparse) == kDkvOneWave) {
     // d <= 64: the kernel in which one wavefront does all four products, same work assignment
     int e = launch_dkv_fr(a, std::is_same<T, __bf16>::value ? 1 : 0, D, causal, dropout, true, kListGroups, s);
     if (e == 0) {
@@ -503,21 +503,28 @@ int launch_td(KArgs a, bool causal, bool dropout, bool sparse, hipStream_t s) {
 
 }  // namespace
 
-int launch_dkv_rs(const KArgs& a, int dtype, int d, bool causal, bool dropout, bool sparse, hipStream_t s) {
+int choose_dkv(const KArgs& a, int d, bool causal, bool dropout, bool sparse) {
   // Problems with d <= 64 take the kernel in which one wavefront does all four products
   // (attn_bwd_dkv_fr.hip; the block-sparse ones from inside launch_td, between the column
   // planning and the finish kernel).
   // (head dimension 16 exists in that kernel only)
-  if (!sparse && d <= 64 && (!force_role_split() || a.dvalid < d)) return launch_dkv_fr(a, dtype, d, causal, dropout, false, 0, s);
+  if (d <= 64 && (!force_role_split() || a.dvalid < d)) return kDkvOneWave;
   // d = 128, dense, no dropout: the one-wavefront kernel with the V block in LDS (attn_bwd_dkv_fr128.hip)
   // (with 64 keys per wavefront where a head has at least two blocks of 256 keys and whole 32-query tiles: attn_bwd_dkv_w64.hip)
   if (!sparse && d == 128 && !dropout && !force_role_split()) {
     // measured against the 32-key kernel: 1 % faster at N = 2048, 5 % at 4096, 7 % at 16384; slower below,
     // and slower under the causal mask at every length (its 256-key work items balance worse)
     const bool w64 = dkv_variant() == 3 || (dkv_variant() == 0 && !causal && a.N >= 2048);
-    if (w64 && a.N >= 512 && a.N % 32 == 0) return launch_dkv_w64(a, dtype, causal, s);
-    return launch_dkv_fr128(a, dtype, causal, s);
+    return w64 && a.N >= 512 && a.N % 32 == 0 ? kDkvOneWave64 : kDkvOneWave128;
   }
+  return kDkvRoleSplit;
+}
+
+int launch_dkv_rs(const KArgs& a, int dtype, int d, bool causal, bool dropout, bool sparse, hipStream_t s) {
+  const int choice = choose_dkv(a, d, causal, dropout, sparse);
+  if (!sparse && choice == kDkvOneWave) return launch_dkv_fr(a, dtype, d, causal, dropout, false, 0, s);
+  if (choice == kDkvOneWave64) return launch_dkv_w64(a, dtype, causal, s);
+  if (choice == kDkvOneWave128) return launch_dkv_fr128(a, dtype, causal, s);
   if (dtype == 0 && d == 32) return launch_td<_Float16, 32>(a, causal, dropout, sparse, s);
   if (dtype == 1 && d == 32) return launch_td<__bf16, 32>(a, causal, dropout, sparse, s);
   if (dtype == 0 && d == 64) return launch_td<_Float16, 64>(a, causal, dropout, sparse, s);

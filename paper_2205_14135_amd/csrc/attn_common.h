@@ -62,6 +62,12 @@ enum { kHeavyBlocks = 24, kSegBlocks = 12, kMaxSegs = 32, kSegHeader = 8, kCompu
 int fwd_variant();
 int dkv_variant();
 
+// Which kernel serves a problem (the launchers use these; attn_debug_kernel_choice reports them).
+enum { kFwdFreeRunning = 0, kFwdTwoGroup = 1 };
+enum { kDkvRoleSplit = 0, kDkvOneWave = 1, kDkvOneWave128 = 2, kDkvOneWave64 = 3 };
+int choose_fwd(const KArgs& a, int d, bool causal, bool dropout, bool sparse);
+int choose_dkv(const KArgs& a, int d, bool causal, bool dropout, bool sparse);
+
 // Launchers (defined in the .hip files).  dtype: 0 fp16, 1 bf16.  Return hipError_t as int.
 int launch_fwd(const KArgs& a, int dtype, int d, bool causal, bool dropout, bool sparse, hipStream_t s);
 // ev: nullptr, or four events: two recorded before the first launch, one after the dQ kernel, one after dK/dV.
@@ -80,7 +86,7 @@ int launch_dkv_w64(const KArgs& a, int dtype, bool causal, hipStream_t s);
 // dense forward with two wavefront groups in ping-pong (attn_fwd_pp.hip); sets its own work items
 int launch_fwd_pp(const KArgs& a, int dtype, int d, bool causal, bool dropout, hipStream_t s);
 // MFMA-only kernel for measuring the sustained matrix rate (attn_probe.hip); *flops = FLOPs launched
-int launch_mfma_rate(int dtype, int iters, float* sink, hipStream_t s, double* flops);
+int launch_mfma_rate(int dtype, int iters, int operand_sets, float* sink, hipStream_t s, double* flops);
 
 #if defined(__HIPCC__)
 // ---------------------------------------------------------------- device helpers

@@ -348,6 +348,17 @@ __global__ void dropout_mask_kernel(const KArgs a, uint8_t* keep) {
 
 }  // namespace
 
+int choose_fwd(const KArgs& a, int d, bool causal, bool dropout, bool sparse) {
+  const int variant = fwd_variant();
+  const int n_qt256 = (a.N + 255) / 256;
+  const int64_t pp_items = (int64_t)a.B * a.H * (causal ? (n_qt256 + 1) / 2 : n_qt256);
+  bool use_pp = d == 128 && pp_items >= kComputeUnits &&
+                (dropout ? causal : (a.N >= 1024 || (causal && a.N >= 512)));
+  if (variant == 1) use_pp = false;
+  if (variant == 2 && d != 32) use_pp = true;
+  return !sparse && use_pp ? kFwdTwoGroup : kFwdFreeRunning;   // (the reasons: see launch_fwd)
+}
+
 int launch_fwd(const KArgs& a, int dtype, int d, bool causal, bool dropout, bool sparse, hipStream_t s) {
   // Which dense d = 128 problems take the two-group ping-pong kernel (attn_fwd_pp.hip), by
   // measurement against this file's kernel (two free-running 4-wave workgroups per compute unit):
@@ -360,14 +371,7 @@ int launch_fwd(const KArgs& a, int dtype, int d, bool causal, bool dropout, bool
   // At d <= 64 the vector ALU work dominates and this file's kernel measured faster at every N;
   // block-sparse problems always take it.  attn_debug_set_variant overrides the choice
   // (comparisons and tests).
-  const int variant = fwd_variant();
-  const int n_qt256 = (a.N + 255) / 256;
-  const int64_t pp_items = (int64_t)a.B * a.H * (causal ? (n_qt256 + 1) / 2 : n_qt256);
-  bool use_pp = d == 128 && pp_items >= kComputeUnits &&
-                (dropout ? causal : (a.N >= 1024 || (causal && a.N >= 512)));
-  if (variant == 1) use_pp = false;
-  if (variant == 2 && d != 32) use_pp = true;
-  if (!sparse && use_pp) return launch_fwd_pp(a, dtype, d, causal, dropout, s);
+  if (choose_fwd(a, d, causal, dropout, sparse) == kFwdTwoGroup) return launch_fwd_pp(a, dtype, d, causal, dropout, s);
   if (dtype == 0 && d == 32) return launch_fwd_td<_Float16, 32>(a, causal, dropout, sparse, s);
   if (dtype == 1 && d == 32) return launch_fwd_td<__bf16, 32>(a, causal, dropout, sparse, s);
   if (dtype == 0 && d == 64) return launch_fwd_td<_Float16, 64>(a, causal, dropout, sparse, s);

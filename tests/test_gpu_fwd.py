@@ -105,8 +105,9 @@ def test_causal_paired_row_blocks_odd_count(N, d):
 def test_mfma_rate_probe_runs_and_reports_its_flops():
     sink = torch.zeros(64, dtype=torch.float32, device="cuda")
     for dtype in ("fp16", "bf16"):
-        flops = binding.attn_debug_mfma_rate(dtype, 100, sink)
-        assert flops == 2.0 * 32 * 32 * 16 * 4 * 100 * 4 * 2048
+        for sets in (1, 4):
+            flops = binding.attn_debug_mfma_rate(dtype, 100, sink, operand_sets=sets)
+            assert flops == 2.0 * 32 * 32 * 16 * 4 * 100 * 4 * 2048
     torch.cuda.synchronize()
     assert float(sink.abs().sum()) == 0.0      # the sink is never written
 

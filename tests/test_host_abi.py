@@ -153,10 +153,32 @@ def test_static_scratch_entry_point_rejects_large_problems(lib):
 
 def test_mfma_rate_probe_arguments(lib):
     v, z = ctypes.c_void_p(0x1000), ctypes.c_void_p(0)
-    assert lib.attn_debug_mfma_rate(binding.ATTN_BF16, 10, z, z, None) == -1
-    assert lib.attn_debug_mfma_rate(7, 10, v, z, None) == -3
-    assert lib.attn_debug_mfma_rate(binding.ATTN_BF16, 0, v, z, None) == -2
-    assert lib.attn_debug_mfma_rate(binding.ATTN_FP16, (1 << 20) + 1, v, z, None) == -2
+    assert lib.attn_debug_mfma_rate(binding.ATTN_BF16, 10, 1, z, z, None) == -1
+    assert lib.attn_debug_mfma_rate(7, 10, 1, v, z, None) == -3
+    assert lib.attn_debug_mfma_rate(binding.ATTN_BF16, 0, 4, v, z, None) == -2
+    assert lib.attn_debug_mfma_rate(binding.ATTN_FP16, (1 << 20) + 1, 1, v, z, None) == -2
+    assert lib.attn_debug_mfma_rate(binding.ATTN_FP16, 10, 3, v, z, None) == -2
+
+
+def test_kernel_choice_query(lib):
+    """The choice the launchers make, asked for without launching (host only)."""
+    binding.attn_debug_set_variant(fwd="auto", dkv="auto")
+    choice = lambda sparse=False, **kw: binding.attn_debug_kernel_choice(_params(**kw), sparse)
+    assert choice(B=4, H=16, N=4096, d=128) == ("fwd_pp_kernel", "dkv_w64_kernel")
+    assert choice(B=4, H=16, N=4096, d=128, causal=1) == ("fwd_pp_kernel", "dkv_fr128_kernel")
+    assert choice(B=4, H=16, N=4096, d=128, dropout_p=0.1) == ("fwd_kernel", "dkv_rs_kernel")
+    assert choice(B=8, H=8, N=1024, d=128, causal=1, dropout_p=0.1) == ("fwd_kernel", "dkv_rs_kernel")   # 128 work items only
+    assert choice(B=16, H=16, N=512, d=64, dropout_p=0.1) == ("fwd_kernel", "dkv_fr_kernel")
+    assert choice(B=1, H=8, N=16384, d=64, sparse=True) == ("fwd_kernel", "dkv_fr_kernel")
+    assert choice(B=4, H=16, N=4096, d=128, sparse=True) == ("fwd_kernel", "dkv_rs_kernel")
+    assert choice(B=4, H=16, N=4010, d=128) == ("fwd_pp_kernel", "dkv_fr128_kernel")      # not whole 32-query tiles
+    binding.attn_debug_set_variant(dkv="w64")
+    assert choice(B=4, H=16, N=1024, d=128, causal=1)[1] == "dkv_w64_kernel"
+    binding.attn_debug_set_variant(dkv="auto")
+    f, k = ctypes.c_int32(), ctypes.c_int32()
+    assert lib.attn_debug_kernel_choice(ctypes.byref(_params(d=7)), 0, ctypes.byref(f), ctypes.byref(k)) == -4
+    assert lib.attn_debug_kernel_choice(ctypes.byref(_params(N=200)), 1, ctypes.byref(f), ctypes.byref(k)) == -2
+    assert lib.attn_debug_kernel_choice(ctypes.byref(_params()), 0, None, None) == -1
 
 
 def test_mask_arguments(lib):
