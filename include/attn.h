@@ -85,7 +85,8 @@ typedef struct {
   int64_t stride_n;          /*   (stride_n >= d, d itself has stride 1)     */
   float softmax_scale;       /* tau: multiplies Q K^T before mask and softmax */
   int32_t causal;            /* != 0: key j is visible to query i iff j <= i */
-  float dropout_p;           /* p_drop in [0,1); 0 switches the generator off */
+  float dropout_p;           /* p_drop in [0,1), applied rounded down to a multiple of 1/256;
+                                below 1/256 the generator is switched off      */
   uint64_t seed;             /* Philox key   (the saved generator state R)   */
   uint64_t offset;           /* low 32 bits enter the Philox counter         */
   int32_t o_fp32;            /* != 0: O is read/written as float32 [B,H,N,d] packed
@@ -102,13 +103,17 @@ typedef struct {
 /*
  * Dropout mask (bit-exact contract, shared with nothing but this text):
  * Philox-4x32 with 10 rounds (Salmon et al., SC'11), key = (seed low word,
- * seed high word), counter = (j / 8, i, b * H + h, offset low word) for query
- * row i and key column j of head (b, h); element (i, j) takes the 16-bit
- * field f = j % 8 of the 128-bit output (bits [16 (f % 2), 16 (f % 2) + 15]
- * of output word f / 2) and is KEPT iff field >= floor((double)dropout_p *
- * 2^16).  Kept probabilities are multiplied by 1 / (1 - dropout_p).  The
- * mask depends on indices only, so the backward pass regenerates it
- * (Appendix B.4, obs. 1).
+ * seed high word), counter = (j / 16, i, b * H + h, offset low word) for query
+ * row i and key column j of head (b, h); element (i, j) takes the 8-bit
+ * field f = j % 16 of the 128-bit output (byte f % 4, i.e. bits [8 (f % 4),
+ * 8 (f % 4) + 7], of output word f / 4) and is KEPT iff field >= T, with
+ * T = floor((double)dropout_p * 2^8).  The dropout applied is therefore the one
+ * with probability T / 256, dropout_p rounded down to a multiple of 1/256
+ * (0.1 -> 25/256; below 1/256 nothing is dropped), and kept probabilities are
+ * multiplied by 256 / (256 - T), the reciprocal of the keep probability, so
+ * that the mask has expectation one.  One generator call decides sixteen
+ * consecutive keys of a query.  The mask depends on indices only, so the
+ * backward pass regenerates it (Appendix B.4, obs. 1).
  */
 
 /*

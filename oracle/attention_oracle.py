@@ -43,6 +43,7 @@ import numpy as np
 __all__ = [
     "philox4x32_10",
     "dropout_threshold",
+    "dropout_effective_p",
     "dropout_keep_mask",
     "visible_mask",
     "forward_head",
@@ -93,16 +94,23 @@ def philox4x32_10(c0, c1, c2, c3, k0, k1):
 
 
 def dropout_threshold(p_drop) -> int:
-    """Integer threshold: an element is KEPT iff its 16-bit field >= threshold.
+    """Integer threshold: an element is KEPT iff its 8-bit field >= threshold.
 
     The probability travels through the C interface as a float32, so the
-    threshold is floor(double(float32(p)) * 2^16); P(drop) = threshold / 2^16,
-    within 2^-16 of p.
+    threshold is floor(double(float32(p)) * 2^8); the dropout actually applied
+    has P(drop) = threshold / 2^8: p rounded down to a multiple of 1/256
+    (dropout_effective_p), and kept entries are scaled by the reciprocal of the
+    matching keep probability, so that E[Z] = 1 exactly.
     """
     p = float(np.float32(p_drop))
     if not (0.0 <= p < 1.0):
         raise ValueError("dropout probability must be in [0, 1)")
-    return int(np.floor(p * 65536.0))
+    return int(np.floor(p * 256.0))
+
+
+def dropout_effective_p(p_drop) -> float:
+    """The drop probability that is really applied: dropout_threshold / 256."""
+    return dropout_threshold(p_drop) / 256.0
 
 
 def dropout_keep_mask(b, h, H, N, p_drop, seed, offset, rows=None):
@@ -111,29 +119,29 @@ def dropout_keep_mask(b, h, H, N, p_drop, seed, offset, rows=None):
     Keying (a reading; the paper only says the generator state is saved and
     the mask regenerated, Appendix B.4 observation 1):
       key     = (seed & 0xffffffff, seed >> 32)
-      counter = (j // 8, i, b * H + h, offset & 0xffffffff)
-      element (i, j) uses the 16-bit field j % 8 of the 128-bit output: field f
-      is bits [16 (f % 2), 16 (f % 2) + 15] of output word f // 2;
+      counter = (j // 16, i, b * H + h, offset & 0xffffffff)
+      element (i, j) uses the 8-bit field j % 16 of the 128-bit output: field f
+      is byte f % 4 (bits [8 (f % 4), 8 (f % 4) + 7]) of output word f // 4;
       keep iff field >= threshold.
-    One generator call therefore decides eight consecutive keys of a query.
+    One generator call therefore decides sixteen consecutive keys of a query.
     i is the query row and j the key column inside the head.  The mask depends
     on indices only: not on tiling, loop order, pass, or other masks.
     """
     if rows is None:
         rows = np.arange(N)
     rows = np.asarray(rows, dtype=np.int64)
-    if p_drop == 0.0:
-        return np.ones((rows.size, N), dtype=bool)
     thr = dropout_threshold(p_drop)
+    if thr == 0:
+        return np.ones((rows.size, N), dtype=bool)
     seed = int(seed) & 0xFFFFFFFFFFFFFFFF
     k0, k1 = seed & 0xFFFFFFFF, seed >> 32
-    ngrp = (N + 7) // 8
+    ngrp = (N + 15) // 16
     jg = np.arange(ngrp, dtype=np.int64)[None, :]
     ii = rows[:, None]
     w = philox4x32_10(jg, ii, b * H + h, int(offset) & 0xFFFFFFFF, k0, k1)
     words = np.stack(w, axis=-1).astype(np.uint32)                       # [rows, ngrp, 4]
-    fields = np.stack([words & np.uint32(0xFFFF), words >> np.uint32(16)], axis=-1)   # [rows, ngrp, 4, 2]
-    fields = fields.reshape(rows.size, ngrp * 8)[:, :N]
+    fields = np.stack([(words >> np.uint32(8 * k)) & np.uint32(0xFF) for k in range(4)], axis=-1)   # [rows, ngrp, 4, 4]
+    fields = fields.reshape(rows.size, ngrp * 16)[:, :N]
     return fields >= np.uint32(thr)
 
 
@@ -172,12 +180,13 @@ def _probabilities(Q, K, tau, vis):
 
 
 def _dropout_factor(p_drop, keep, shape):
-    """Z of Algorithm 4: 1/(1-p) where kept, 0 where dropped; all ones when p = 0."""
-    if p_drop > 0.0:
+    """Z of Algorithm 4: 1/(1-p) where kept, 0 where dropped, with p the drop probability that
+    is really applied (dropout_effective_p); all ones when that is 0."""
+    p_eff = dropout_effective_p(p_drop)
+    if p_eff > 0.0:
         if keep is None:
             raise ValueError("keep mask required when p_drop > 0")
-        scale = 1.0 / (1.0 - float(np.float32(p_drop)))
-        return np.where(keep, scale, 0.0)
+        return np.where(keep, 1.0 / (1.0 - p_eff), 0.0)
     return np.ones(shape)
 
 

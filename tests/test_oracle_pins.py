@@ -61,10 +61,13 @@ def test_philox_scalar_reimplementation():
 
 
 def test_dropout_threshold_from_float32():
-    assert orc.dropout_threshold(0.1) == 6553               # floor(float32(0.1) * 2^16)
-    assert orc.dropout_threshold(0.5) == 2 ** 15
-    assert orc.dropout_threshold(0.999) == 65470            # float32(0.999) = 0.99900001287...
+    assert orc.dropout_threshold(0.1) == 25                 # floor(float32(0.1) * 2^8)
+    assert orc.dropout_threshold(0.5) == 2 ** 7
+    assert orc.dropout_threshold(0.999) == 255              # float32(0.999) * 256 = 255.744...
+    assert orc.dropout_threshold(0.25) == 64 and orc.dropout_threshold(0.2) == 51
     assert orc.dropout_threshold(0.0) == 0
+    assert orc.dropout_threshold(0.0039) == 0               # below 1/256: nothing is dropped
+    assert orc.dropout_effective_p(0.1) == 25 / 256 and orc.dropout_effective_p(0.25) == 0.25
     with pytest.raises(ValueError):
         orc.dropout_threshold(1.0)
 
@@ -74,11 +77,11 @@ def test_dropout_mask_keying_and_rate():
     p, seed, off = 0.1, 0x123456789ABCDEF0, 7
     thr = orc.dropout_threshold(p)
     keep = orc.dropout_keep_mask(1, 2, H, N, p, seed, off)
-    # element (i, j): counter (j//8, i, b*H+h, offset), 16-bit field j%8 (low half of a word first)
-    for (i, j) in [(0, 0), (5, 3), (17, 42), (63, 63), (31, 4), (2, 15), (9, 8)]:
-        w = orc.philox4x32_10(j // 8, i, 1 * H + 2, off, seed & 0xFFFFFFFF, seed >> 32)
-        f = j % 8
-        field = (int(w[f // 2]) >> (16 * (f % 2))) & 0xFFFF
+    # element (i, j): counter (j//16, i, b*H+h, offset), 8-bit field j%16 (lowest byte of a word first)
+    for (i, j) in [(0, 0), (5, 3), (17, 42), (63, 63), (31, 4), (2, 15), (9, 8), (40, 16), (40, 31), (7, 55)]:
+        w = orc.philox4x32_10(j // 16, i, 1 * H + 2, off, seed & 0xFFFFFFFF, seed >> 32)
+        f = j % 16
+        field = (int(w[f // 4]) >> (8 * (f % 4))) & 0xFF
         assert keep[i, j] == (field >= thr)
     # different heads / seeds / offsets give different masks
     assert (keep != orc.dropout_keep_mask(1, 1, H, N, p, seed, off)).any()
@@ -90,9 +93,29 @@ def test_dropout_mask_keying_and_rate():
     # keep rate within 4 sigma on a larger sample
     big = orc.dropout_keep_mask(0, 0, 1, 512, p, 99, 0)
     n = big.size
-    sigma = math.sqrt(p * (1 - p) / n)
-    assert abs(big.mean() - (1 - p)) < 4 * sigma
+    q = thr / 256                      # the probability really applied: 25/256 for p = 0.1
+    sigma = math.sqrt(q * (1 - q) / n)
+    assert abs(big.mean() - (1 - q)) < 4 * sigma
     assert orc.dropout_keep_mask(0, 0, 1, 16, 0.0, 1, 0).all()
+    assert orc.dropout_keep_mask(0, 0, 1, 16, 0.003, 1, 0).all()     # rounds down to no dropout
+
+
+def test_dropout_rate_and_scale_follow_the_rounded_probability():
+    """p travels as float32 and is rounded down to a multiple of 1/256: the keep rate is 1 - thr/256 and
+    kept entries are scaled by its reciprocal, so E[Z] = 1 (with 1/(1 - p) instead, p = 0.3 would be
+    off by 0.45 %, five sigma of this sample)."""
+    N = 1024
+    for p in (0.1, 0.3):
+        thr = orc.dropout_threshold(p)
+        keep = orc.dropout_keep_mask(0, 0, 1, N, p, 1234, 0)
+        q = thr / 256
+        sigma = math.sqrt(q * (1 - q) / keep.size)
+        assert abs(keep.mean() - (1 - q)) < 4 * sigma
+        Q, K, V = rnd(8, 4, seed=1), rnd(8, 4, seed=2), rnd(8, 4, seed=3)
+        _, _, _, Z = orc.forward_head(Q, K, V, 0.5, p_drop=p, keep=keep[:8, :8], return_p=True)
+        assert set(np.unique(Z)) <= {0.0, 256.0 / (256 - thr)}
+        z_mean = keep.mean() * 256.0 / (256 - thr)
+        assert abs(z_mean - 1.0) < 4 * sigma / (1 - q)
 
 
 # ------------------------------------------------------------ closed forms --
