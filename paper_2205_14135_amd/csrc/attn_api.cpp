@@ -75,8 +75,10 @@ int check_params(const attn_params* p, Checked* out) {
   k.dvalid = p->d;
   k.tau = p->softmax_scale;
   k.scale_log2 = (float)((double)p->softmax_scale * 1.4426950408889634);
-  k.keep_scale = 1.0f / (1.0f - p->dropout_p);
-  k.drop_thr = (uint32_t)std::floor((double)p->dropout_p * 65536.0);   // 16-bit fields
+  // 8-bit fields: the dropout applied has probability T / 256, and kept entries are scaled by the
+  // reciprocal of the matching keep probability
+  k.drop_thr = (uint32_t)std::floor((double)p->dropout_p * 256.0);
+  k.keep_scale = 256.0f / (256.0f - (float)k.drop_thr);
   k.seed_lo = (uint32_t)(p->seed & 0xFFFFFFFFu);
   k.seed_hi = (uint32_t)(p->seed >> 32);
   k.offset_lo = (uint32_t)(p->offset & 0xFFFFFFFFu);
@@ -85,7 +87,7 @@ int check_params(const attn_params* p, Checked* out) {
   out->dtype = p->dtype;
   out->d = p->d == 16 ? 32 : p->d;   // head dimension 16 runs on the d = 32 kernels (zero upper half on chip)
   out->causal = p->causal != 0;
-  out->dropout = p->dropout_p > 0.0f;
+  out->dropout = k.drop_thr > 0;   // below 1/256 nothing is dropped: the generator stays off
   out->stream = (hipStream_t)p->stream;
   return ATTN_OK;
 }

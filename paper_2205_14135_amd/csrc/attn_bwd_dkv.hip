@@ -202,48 +202,17 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
       __builtin_amdgcn_sched_barrier(0);
     }
   };
-  // Dropout bits in this layout.  A draw decides eight consecutive keys of one query row, i.e.
-  // the eight lanes r = 8 m .. 8 m + 7 of one half-wave (same g); those lanes need the draws of
-  // the same 32 rows (2 qb x 4 i4 x 4 e).  Lane u = r % 8 draws the four rows (qb = u / 4,
-  // i4 = 0..3, e = u % 4) and keeps, for each, the eight key bits: mine = bits [8 i4 + key].
-  // keep_words() then collects, for every (qb, e), the word of lane 4 qb + e of the group, shifted
-  // so that bit 8 i4 is this lane's key.
-  auto keep_words = [&](uint32_t mine, uint32_t (&kw)[2][4]) {
-    const int u = r & 7;
-    // the word of the lane at the mirrored position 7 - u (other quad of the group)
-    const uint32_t mirrored = (uint32_t)__builtin_amdgcn_mov_dpp((int)mine, 0x141, 0xF, 0xF, true);   // row_half_mirror
-    uint32_t own[4], oth[4];
-    own[0] = (uint32_t)__builtin_amdgcn_mov_dpp((int)mine, 0x00, 0xF, 0xF, true);
-    own[1] = (uint32_t)__builtin_amdgcn_mov_dpp((int)mine, 0x55, 0xF, 0xF, true);
-    own[2] = (uint32_t)__builtin_amdgcn_mov_dpp((int)mine, 0xAA, 0xF, 0xF, true);
-    own[3] = (uint32_t)__builtin_amdgcn_mov_dpp((int)mine, 0xFF, 0xF, 0xF, true);
-    // quad position x of the mirrored words holds the other quad's element 3 - x
-    oth[3] = (uint32_t)__builtin_amdgcn_mov_dpp((int)mirrored, 0x00, 0xF, 0xF, true);
-    oth[2] = (uint32_t)__builtin_amdgcn_mov_dpp((int)mirrored, 0x55, 0xF, 0xF, true);
-    oth[1] = (uint32_t)__builtin_amdgcn_mov_dpp((int)mirrored, 0xAA, 0xF, 0xF, true);
-    oth[0] = (uint32_t)__builtin_amdgcn_mov_dpp((int)mirrored, 0xFF, 0xF, 0xF, true);
-    const bool upper = (u & 4) != 0;   // this lane sits in the group's second quad (the qb = 1 drawers)
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      kw[0][e] = (upper ? oth[e] : own[e]) >> u;
-      kw[1][e] = (upper ? own[e] : oth[e]) >> u;
-    }
-  };
+  // Dropout bits in this layout: see draw_keep_lane_key() / keep_words_lane_key() in attn_common.h.
+  const int kbit = r & 15;   // position of this lane's key in the 16-key group of a draw
+  auto keep_words = [&](uint32_t mine, KeepLK& kw) { kw = keep_words_lane_key(mine); };
   auto draw_keep = [&](int i0) {
-    uint32_t mine = 0;
-    const int u = r & 7;
-#pragma unroll
-    for (int m = 0; m < 4; ++m) {
-      const uint32_t qrow = (uint32_t)(i0 + 32 * (u >> 2) + 8 * m + 4 * g + (u & 3));
-      mine |= philox_keep8((uint32_t)kj >> 3, qrow, (uint32_t)bh, a.offset_lo, a.seed_lo, a.seed_hi, a.drop_thr) << (8 * m);
-    }
-    return mine;
+    return draw_keep_lane_key(i0, kj, r, g, bh, a.offset_lo, a.seed_lo, a.seed_hi, a.drop_thr);
   };
 
   // ---- role A, tile with first query i0, buffers (q3, p2)
   auto role_a = [&](int i0, int q4, int g3, int p2) {
     row_product(Qs[q4], false, nullptr);                         // S = Q K^T
-    uint32_t kw[2][4] = {{0, 0, 0, 0}, {0, 0, 0, 0}};
+    KeepLK kw = {};
     if constexpr (DROPOUT) {
       const uint32_t mine = draw_keep(i0);
       Kw[p2][pair][lane] = mine;   // role B regenerates nothing: it reads the drawn bits
@@ -272,8 +241,7 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
           pfull[cc][t] = (T)p;
           ph[cc][t] = (_Float16)p;
           if constexpr (DROPOUT) {
-            const bool keep = (kw[qb][e] >> (8 * i4)) & 1u;
-            pf[cc][t] = (T)(keep ? p : 0.f);
+            pf[cc][t] = (T)keep_or_zero(p, keep_mask_lane_key(kw.w[i4][e], kbit + 16 * qb));
           }
         }
       }
@@ -284,7 +252,7 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
   };
   // ---- role B, second half for the previous tile: dS from sd (= dP) and A's P, then dK
   auto role_b_ds_dk = [&](int q4, int p2) {
-    uint32_t kw[2][4] = {{0, 0, 0, 0}, {0, 0, 0, 0}};
+    KeepLK kw = {};
     if constexpr (DROPOUT) keep_words(Kw[p2][pair][lane], kw);
     f16x8 pin[4];
     T8 dsf[4];
@@ -302,8 +270,7 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
           const int cc = 2 * qb + (i4 >> 1), t = 4 * (i4 & 1) + e;
           float dpv = sd[qb][i];   // without dropout: already dP - D
           if constexpr (DROPOUT) {
-            const bool keep = (kw[qb][e] >> (8 * i4)) & 1u;
-            dpv = (keep ? dpv * a.keep_scale : 0.f) + d4[e];
+            dpv = keep_or_zero(dpv * a.keep_scale, keep_mask_lane_key(kw.w[i4][e], kbit + 16 * qb)) + d4[e];
           }
           // (an fma with an fp16 operand is one v_fma_mix_f32: the half is widened inside the instruction)
           dsf[cc][t] = (T)__builtin_fmaf((float)pin[cc][t], dpv, 0.f);

@@ -207,38 +207,10 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr_kernel(const KArgs a) {
       __builtin_amdgcn_sched_barrier(0);
     }
   };
-  // Dropout bits in this layout (same scheme as attn_bwd_dkv.hip).  A draw decides eight
-  // consecutive keys of one query row, i.e. the eight lanes r = 8 m .. 8 m + 7 of one half-wave;
-  // lane u = r % 8 draws the four rows (qb = u / 4, i4 = 0..3, e = u % 4), and the group exchanges
-  // the words by DPP so that kw[qb][e] bit 8 i4 is this lane's key for row (qb, i4, e).
-  auto keep_words = [&](uint32_t mine, uint32_t (&kw)[2][4]) {
-    const int u = r & 7;
-    const uint32_t mirrored = (uint32_t)__builtin_amdgcn_mov_dpp((int)mine, 0x141, 0xF, 0xF, true);   // row_half_mirror
-    uint32_t own[4], oth[4];
-    own[0] = (uint32_t)__builtin_amdgcn_mov_dpp((int)mine, 0x00, 0xF, 0xF, true);
-    own[1] = (uint32_t)__builtin_amdgcn_mov_dpp((int)mine, 0x55, 0xF, 0xF, true);
-    own[2] = (uint32_t)__builtin_amdgcn_mov_dpp((int)mine, 0xAA, 0xF, 0xF, true);
-    own[3] = (uint32_t)__builtin_amdgcn_mov_dpp((int)mine, 0xFF, 0xF, 0xF, true);
-    oth[3] = (uint32_t)__builtin_amdgcn_mov_dpp((int)mirrored, 0x00, 0xF, 0xF, true);
-    oth[2] = (uint32_t)__builtin_amdgcn_mov_dpp((int)mirrored, 0x55, 0xF, 0xF, true);
-    oth[1] = (uint32_t)__builtin_amdgcn_mov_dpp((int)mirrored, 0xAA, 0xF, 0xF, true);
-    oth[0] = (uint32_t)__builtin_amdgcn_mov_dpp((int)mirrored, 0xFF, 0xF, 0xF, true);
-    const bool upper = (u & 4) != 0;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      kw[0][e] = (upper ? oth[e] : own[e]) >> u;
-      kw[1][e] = (upper ? own[e] : oth[e]) >> u;
-    }
-  };
+  // Dropout bits in this layout: see draw_keep_lane_key() / keep_words_lane_key() in attn_common.h.
+  const int kbit = r & 15;   // position of this lane's key in the 16-key group of a draw
   auto draw_keep = [&](int i0) {
-    uint32_t mine = 0;
-    const int u = r & 7;
-#pragma unroll
-    for (int m = 0; m < 4; ++m) {
-      const uint32_t qrow = (uint32_t)(i0 + 32 * (u >> 2) + 8 * m + 4 * g + (u & 3));
-      mine |= philox_keep8((uint32_t)kj >> 3, qrow, (uint32_t)bh, a.offset_lo, a.seed_lo, a.seed_hi, a.drop_thr) << (8 * m);
-    }
-    return mine;
+    return draw_keep_lane_key(i0, kj, r, g, bh, a.offset_lo, a.seed_lo, a.seed_hi, a.drop_thr);
   };
 
   // ---- pipeline over the query tiles of this key block: tile t + 1 streams in while t is used
@@ -257,8 +229,8 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr_kernel(const KArgs a) {
     if (!CAUSAL || i0 + TILE - 1 >= kw0) {
       f32x16 s[2], dp[2];
       row_product(Qs0 + buf * TILE * D, kf, false, nullptr, s);                // S = Q K^T
-      uint32_t kw[2][4] = {{0, 0, 0, 0}, {0, 0, 0, 0}};
-      if constexpr (DROPOUT) keep_words(draw_keep(i0), kw);
+      uint32_t drawn = 0;   // this lane's packed keep bits; the words of a row group are fetched where they are used
+      if constexpr (DROPOUT) drawn = draw_keep(i0);
       if (kw0 + 32 > len) {   // this wavefront holds padded keys: their logits become -inf, hence P = 0
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb)
@@ -269,9 +241,11 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr_kernel(const KArgs a) {
       // P = exp(S - L), kept in fp32 in s[] for dS; the 16-bit (dropped) copy feeds dV
       T8 pf[4];
 #pragma unroll
-      for (int qb = 0; qb < 2; ++qb)
+      for (int i4 = 0; i4 < 4; ++i4) {
+        KeepLK4 kw = {};
+        if constexpr (DROPOUT) kw = keep_words_lane_key(drawn, i4);
 #pragma unroll
-        for (int i4 = 0; i4 < 4; ++i4) {
+        for (int qb = 0; qb < 2; ++qb) {
           const f32x4 l4 = *(const f32x4*)(Ls0 + buf * TILE + 32 * qb + 8 * i4 + 4 * g);
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
@@ -281,21 +255,27 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr_kernel(const KArgs a) {
             s[qb][i] = p;
             const int cc = 2 * qb + (i4 >> 1), tt = 4 * (i4 & 1) + e;
             if constexpr (DROPOUT) {
-              const bool keep = (kw[qb][e] >> (8 * i4)) & 1u;
-              pf[cc][tt] = (T)(keep ? p : 0.f);
+              pf[cc][tt] = (T)keep_or_zero(p, keep_mask_lane_key(kw.w[e], kbit + 16 * qb));
             } else {
               pf[cc][tt] = (T)p;
             }
           }
         }
+      }
       col_product(Gs0 + buf * TILE * D, pf, dv);                          // dV^T += dO^T P_dropped
       // dP = dO V^T; without dropout it starts from -D, so the result is dP - D
       row_product(Gs0 + buf * TILE * D, vf, !DROPOUT, Ds0 + buf * TILE, dp);
       T8 dsf[4];
+      // (the row broadcasts are repeated here rather than kept from the P pass: sixteen registers
+      // held across the dP product would spill; the empty statement keeps the compiler from
+      // merging the two sets)
+      if constexpr (DROPOUT) asm volatile("" : "+v"(drawn));
 #pragma unroll
-      for (int qb = 0; qb < 2; ++qb)
+      for (int i4 = 0; i4 < 4; ++i4) {
+        KeepLK4 kw = {};
+        if constexpr (DROPOUT) kw = keep_words_lane_key(drawn, i4);
 #pragma unroll
-        for (int i4 = 0; i4 < 4; ++i4) {
+        for (int qb = 0; qb < 2; ++qb) {
           f32x4 d4 = {0.f, 0.f, 0.f, 0.f};
           if constexpr (DROPOUT) d4 = *(const f32x4*)(Ds0 + buf * TILE + 32 * qb + 8 * i4 + 4 * g);   // -D_i
 #pragma unroll
@@ -304,12 +284,12 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr_kernel(const KArgs a) {
             const int cc = 2 * qb + (i4 >> 1), tt = 4 * (i4 & 1) + e;
             float dpv = dp[qb][i];
             if constexpr (DROPOUT) {
-              const bool keep = (kw[qb][e] >> (8 * i4)) & 1u;
-              dpv = (keep ? dpv * a.keep_scale : 0.f) + d4[e];
+              dpv = keep_or_zero(dpv * a.keep_scale, keep_mask_lane_key(kw.w[e], kbit + 16 * qb)) + d4[e];
             }
             dsf[cc][tt] = (T)(s[qb][i] * dpv);
           }
         }
+      }
       col_product(Qs0 + buf * TILE * D, dsf, dk);                         // dK^T += Q^T dS
     }
     wait_async_copies();

@@ -40,7 +40,7 @@ struct KArgs {
   float tau;               // softmax scale
   float scale_log2;        // tau * log2(e)
   float keep_scale;        // 1 / (1 - p_drop)
-  uint32_t drop_thr;       // keep iff 16-bit philox field >= drop_thr
+  uint32_t drop_thr;       // T: keep iff 8-bit philox field >= T (1..255 when dropout is on)
   uint32_t seed_lo, seed_hi, offset_lo;
   int o_fp32;
   int n_items;             // work items (B*H*tiles)
@@ -139,8 +139,9 @@ __device__ __forceinline__ u32x4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_
   for (int r = 0; r < 10; ++r) {
     const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
     const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
-    const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
-    const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+    // the two three-way exclusive ors of a round, one instruction each
+    const uint32_t n0 = __builtin_amdgcn_bitop3_b32((uint32_t)(p1 >> 32), c1, k0, 0x96);
+    const uint32_t n2 = __builtin_amdgcn_bitop3_b32((uint32_t)(p0 >> 32), c3, k1, 0x96);
     c1 = (uint32_t)p1; c3 = (uint32_t)p0; c0 = n0; c2 = n2;
     k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
   }
@@ -148,18 +149,43 @@ __device__ __forceinline__ u32x4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_
   return r;
 }
 
-// Dropout draw (see the contract in include/attn.h): one Philox call decides the eight keys
-// 8 g8 .. 8 g8 + 7 of query row i; bit f of the result is set iff key 8 g8 + f is KEPT.
-__device__ __forceinline__ uint32_t philox_keep8(uint32_t g8, uint32_t i, uint32_t bh, uint32_t offset_lo,
-                                                uint32_t seed_lo, uint32_t seed_hi, uint32_t thr16) {
-  const u32x4 w = philox4x32_10(g8, i, bh, offset_lo, seed_lo, seed_hi);
-  uint32_t m = 0;
+// Dropout draw (see the contract in include/attn.h): one Philox call decides the sixteen keys
+// 16 g16 .. 16 g16 + 15 of query row i; key 16 g16 + f is KEPT iff byte f % 4 of word f / 4 of the
+// result is >= T.
+__device__ __forceinline__ u32x4 philox_draw16(uint32_t g16, uint32_t i, uint32_t bh, uint32_t offset_lo,
+                                               uint32_t seed_lo, uint32_t seed_hi) {
+  return philox4x32_10(g16, i, bh, offset_lo, seed_lo, seed_hi);
+}
+// The threshold test of the four 8-bit fields of a word, two at a time: field >= T iff
+// field + (256 - T) carries out of its eight bits, and in 16-bit lanes the carry of fields 0 / 2
+// (even) or 1 / 3 (odd) lands in bit 8 / bit 24, alone in its byte.  carry2 = (256 - T) * 0x00010001.
+struct Keep4 { uint32_t even, odd; };
+__device__ __forceinline__ uint32_t dropout_carry2(uint32_t thr8) { return (256u - thr8) * 0x00010001u; }
+__device__ __forceinline__ Keep4 keep4(uint32_t w, uint32_t carry2) {
+  Keep4 k;
+  k.even = (w & 0x00FF00FFu) + carry2;
+  k.odd = __builtin_amdgcn_perm(0u, w, 0x0C030C01u) + carry2;   // (w >> 8) & 0x00FF00FF in one instruction
+  return k;
+}
+// all ones if field f (0..3, a constant) of the word was kept, else zero
+__device__ __forceinline__ uint32_t keep_mask(const Keep4& k, int f) {
+  return (uint32_t)__builtin_amdgcn_sbfe((int)((f & 1) ? k.odd : k.even), 8 + 16 * (f >> 1), 1);
+}
+__device__ __forceinline__ float keep_or_zero(float x, uint32_t mask) {
+  return __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, x) & mask);
+}
+// the sixteen keep bits of a call: bit f set iff key 16 g16 + f is kept
+__device__ __forceinline__ uint32_t keep_bits16(const u32x4& w, uint32_t carry2) {
+  uint32_t bits = 0;
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
-    m |= ((w[t] & 0xFFFFu) >= thr16 ? 1u : 0u) << (2 * t);
-    m |= ((w[t] >> 16) >= thr16 ? 1u : 0u) << (2 * t + 1);
+    const Keep4 k = keep4(w[t], carry2);
+    // the four flag bytes (0 or 1) of the word side by side: fields 0, 1, 2, 3
+    const uint32_t flags = __builtin_amdgcn_perm(k.odd, k.even, 0x07030501u);
+    const uint32_t nib = (flags | (flags >> 7) | (flags >> 14) | (flags >> 21)) & 0xFu;
+    bits |= nib << (4 * t);
   }
-  return m;
+  return bits;
 }
 
 // value of the lane 32 positions away (wave64)
@@ -171,25 +197,83 @@ __device__ __forceinline__ float xchg32(float x) {
   return __builtin_bit_cast(float, other);
 }
 
-// Keep bits of a 64-key tile in the "lane = query" layout (forward, dQ).  The two lanes of a
-// query (g = 0 / 1) need the same eight draws (key groups k0/8 .. k0/8 + 7) and different halves
-// of each: lane g draws the groups with i4 % 2 == g and the pair swaps the result words.
-// Returns {even, odd}: the draws of the groups with even / odd i4, already shifted so that the bit
-// of element (kb, i4, e) of THIS lane is bit 8 (2 kb + i4 / 2) + e of word i4 % 2.
-struct KeepLQ { uint32_t even, odd; };
+// Dropout words of a 64-key tile in the "lane = query" layout (forward, dQ).  A call decides 16
+// consecutive keys of the lane's query: the four calls of a tile are key block kb = 0, 1 times half
+// 0, 1 of its 32 keys, and word w of a call holds keys 4 w .. 4 w + 3 of that half, which belong to
+// lane g' = w % 2 of the query's two lanes, row group i4 = 2 half + w / 2.  Lane g draws half g of
+// both key blocks, and the pair exchanges the words that belong to the other lane (four swaps serve
+// both directions).  Result: byte e of w[kb][i4] decides element (kb, i4, e) of THIS lane.
+struct KeepLQ { uint32_t w[2][4]; };
 __device__ __forceinline__ KeepLQ keep_tile_lane_query(int k0, int qi, int bh, int g, uint32_t offset_lo,
-                                                       uint32_t seed_lo, uint32_t seed_hi, uint32_t thr16) {
+                                                       uint32_t seed_lo, uint32_t seed_hi) {
+  KeepLQ k;
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb) {
+    const u32x4 r = philox_draw16((uint32_t)(k0 >> 4) + 2 * kb + g, (uint32_t)qi, (uint32_t)bh, offset_lo, seed_lo, seed_hi);
+    // v_permlane32_swap(x, y): the upper 32 lanes' x and the lower 32 lanes' y change places
+    auto s01 = __builtin_amdgcn_permlane32_swap(r[0], r[1], false, false);
+    auto s23 = __builtin_amdgcn_permlane32_swap(r[2], r[3], false, false);
+    // lane 0 now holds (own word 0, lane 1's word 0, own word 2, lane 1's word 2) = row groups 0, 2, 1, 3;
+    // lane 1 holds (lane 0's word 1, own word 1, lane 0's word 3, own word 3) = row groups 0, 2, 1, 3
+    k.w[kb][0] = s01[0]; k.w[kb][2] = s01[1]; k.w[kb][1] = s23[0]; k.w[kb][3] = s23[1];
+  }
+  return k;
+}
+
+// Dropout in the "lane = key" layout (dK / dV kernels): a wavefront holds 32 keys (lane r, twice:
+// g = 0, 1) times 64 queries; lane (r, g) holds its key for the queries i0 + 32 qb + 8 i4 + 4 g + e.
+// A call decides 16 consecutive keys of one query, i.e. the 16 lanes of one row of the wavefront
+// (same g, same r / 16), which all need the draws of the same 32 queries.  Lane u = r % 16 of a row
+// draws the two queries (qb = 0, 1; i4 = u / 4, e = u % 4) and packs their keep bits into one word,
+// bit 16 qb + key.  keep_words_lane_key() then hands every lane the words of all 16 lanes of its
+// row (a row broadcast through the LDS crossbar, no memory involved): w[i4][e] bit (r % 16) + 16 qb
+// is this lane's key for query (qb, i4, e).
+__device__ __forceinline__ uint32_t draw_keep_lane_key(int i0, int kj, int r, int g, int bh, uint32_t offset_lo,
+                                                       uint32_t seed_lo, uint32_t seed_hi, uint32_t thr8) {
+  const int u = r & 15;
+  const uint32_t carry2 = dropout_carry2(thr8);
   uint32_t mine = 0;
 #pragma unroll
-  for (int n = 0; n < 4; ++n) {   // n = 2 kb + i4 / 2, with i4 = 2 (n % 2) + g
-    const uint32_t g8 = (uint32_t)(k0 >> 3) + 4 * (n >> 1) + 2 * (n & 1) + g;
-    mine |= philox_keep8(g8, (uint32_t)qi, (uint32_t)bh, offset_lo, seed_lo, seed_hi, thr16) << (8 * n);
+  for (int qb = 0; qb < 2; ++qb) {
+    const uint32_t qrow = (uint32_t)(i0 + 32 * qb + 8 * (u >> 2) + 4 * g + (u & 3));
+    const u32x4 w = philox_draw16((uint32_t)kj >> 4, qrow, (uint32_t)bh, offset_lo, seed_lo, seed_hi);
+    mine |= keep_bits16(w, carry2) << (16 * qb);
   }
-  const uint32_t theirs = __builtin_bit_cast(uint32_t, xchg32(__builtin_bit_cast(float, mine)));
-  KeepLQ k;
-  k.even = (g == 0 ? mine : theirs) >> (4 * g);
-  k.odd = (g == 1 ? mine : theirs) >> (4 * g);
+  return mine;
+}
+struct KeepLK { uint32_t w[4][4]; };
+template <int SRC> __device__ __forceinline__ uint32_t row16_broadcast(uint32_t x) {
+  // ds_swizzle, bit mode within 32 lanes: source lane = (lane & 0x10) | SRC
+  return (uint32_t)__builtin_amdgcn_ds_swizzle((int)x, 0x10 | (SRC << 5));
+}
+__device__ __forceinline__ KeepLK keep_words_lane_key(uint32_t mine) {
+  KeepLK k;
+  k.w[0][0] = row16_broadcast<0>(mine);   k.w[0][1] = row16_broadcast<1>(mine);
+  k.w[0][2] = row16_broadcast<2>(mine);   k.w[0][3] = row16_broadcast<3>(mine);
+  k.w[1][0] = row16_broadcast<4>(mine);   k.w[1][1] = row16_broadcast<5>(mine);
+  k.w[1][2] = row16_broadcast<6>(mine);   k.w[1][3] = row16_broadcast<7>(mine);
+  k.w[2][0] = row16_broadcast<8>(mine);   k.w[2][1] = row16_broadcast<9>(mine);
+  k.w[2][2] = row16_broadcast<10>(mine);  k.w[2][3] = row16_broadcast<11>(mine);
+  k.w[3][0] = row16_broadcast<12>(mine);  k.w[3][1] = row16_broadcast<13>(mine);
+  k.w[3][2] = row16_broadcast<14>(mine);  k.w[3][3] = row16_broadcast<15>(mine);
   return k;
+}
+// The four words of row group i4 only (i4 a constant after unrolling), for kernels that cannot
+// afford to hold all sixteen: they fetch a row group where they use it.
+struct KeepLK4 { uint32_t w[4]; };
+__device__ __forceinline__ KeepLK4 keep_words_lane_key(uint32_t mine, int i4) {
+  KeepLK4 k;
+  switch (i4) {
+    case 0: k.w[0] = row16_broadcast<0>(mine); k.w[1] = row16_broadcast<1>(mine); k.w[2] = row16_broadcast<2>(mine); k.w[3] = row16_broadcast<3>(mine); break;
+    case 1: k.w[0] = row16_broadcast<4>(mine); k.w[1] = row16_broadcast<5>(mine); k.w[2] = row16_broadcast<6>(mine); k.w[3] = row16_broadcast<7>(mine); break;
+    case 2: k.w[0] = row16_broadcast<8>(mine); k.w[1] = row16_broadcast<9>(mine); k.w[2] = row16_broadcast<10>(mine); k.w[3] = row16_broadcast<11>(mine); break;
+    default: k.w[0] = row16_broadcast<12>(mine); k.w[1] = row16_broadcast<13>(mine); k.w[2] = row16_broadcast<14>(mine); k.w[3] = row16_broadcast<15>(mine); break;
+  }
+  return k;
+}
+// all ones if this lane's key is kept for query (qb, i4, e); bit = (r % 16) + 16 qb
+__device__ __forceinline__ uint32_t keep_mask_lane_key(uint32_t word, int bit) {
+  return (uint32_t)__builtin_amdgcn_sbfe((int)word, bit, 1);
 }
 
 // Work-item index for this workgroup: consecutive items share an XCD (workgroups are

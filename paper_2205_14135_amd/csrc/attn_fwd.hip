@@ -217,14 +217,16 @@ __global__ __launch_bounds__(NT, 2) void fwd_kernel(const KArgs a) {
           part[cc] = sum8(all, 0.f);
         }
         lr_run += (part[0] + part[1]) + (part[2] + part[3]);
-        const KeepLQ kq = keep_tile_lane_query(k0, qi, bh, g, a.offset_lo, a.seed_lo, a.seed_hi, a.drop_thr);
+        const KeepLQ kq = keep_tile_lane_query(k0, qi, bh, g, a.offset_lo, a.seed_lo, a.seed_hi);
+        const uint32_t carry2 = dropout_carry2(a.drop_thr);
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-          for (int i4 = 0; i4 < 4; ++i4)
+          for (int i4 = 0; i4 < 4; ++i4) {
+            const Keep4 k4 = keep4(kq.w[kb][i4], carry2);
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
-              if ((((i4 & 1) ? kq.odd : kq.even) >> (8 * (2 * kb + (i4 >> 1)) + e) & 1u) == 0) s[kb][4 * i4 + e] = 0.f;
+            for (int e = 0; e < 4; ++e) s[kb][4 * i4 + e] = keep_or_zero(s[kb][4 * i4 + e], keep_mask(k4, e));
+          }
       }
       // ---- P^T fragments (B operand): 16-key chunk cc = 2 kb + half
       T8 pf[4];
@@ -319,28 +321,27 @@ int launch_fwd_td(const KArgs& a_in, bool causal, bool dropout, bool sparse, hip
   return (int)hipErrorInvalidValue;
 }
 
-// keep[bh][i][j] for the test hook: one thread per group of eight consecutive keys
+// keep[bh][i][j] for the test hook: one thread per group of sixteen consecutive keys
 __global__ void dropout_mask_kernel(const KArgs a, uint8_t* keep) {
-  const int64_t ngrp = ((int64_t)a.N + 7) / 8;
+  const int64_t ngrp = ((int64_t)a.N + 15) / 16;
   const int64_t total = (int64_t)a.B * a.H * a.N * ngrp;
   for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
        idx += (int64_t)gridDim.x * blockDim.x) {
-    const uint32_t g8 = (uint32_t)(idx % ngrp);
+    const uint32_t g16 = (uint32_t)(idx % ngrp);
     const uint32_t i = (uint32_t)((idx / ngrp) % a.N);
     const uint32_t bh = (uint32_t)(idx / (ngrp * a.N));
-    const uint32_t m = philox_keep8(g8, i, bh, a.offset_lo, a.seed_lo, a.seed_hi, a.drop_thr);
-    uint32_t lo = 0, hi = 0;
+    const u32x4 w = philox_draw16(g16, i, bh, a.offset_lo, a.seed_lo, a.seed_hi);
+    // (when dropout rounds down to nothing the kernels do not draw at all: everything is kept)
+    const uint32_t m = a.drop_thr == 0 ? 0xFFFFu : keep_bits16(w, dropout_carry2(a.drop_thr));
+    uint8_t* dst = keep + ((int64_t)bh * a.N + i) * a.N + 16 * (int64_t)g16;
+    const int n = min(16, a.N - 16 * (int)g16);
+    if (n == 16 && a.N % 4 == 0) {
 #pragma unroll
-    for (int f = 0; f < 4; ++f) {
-      lo |= ((m >> f) & 1u) << (8 * f);
-      hi |= ((m >> (4 + f)) & 1u) << (8 * f);
-    }
-    if (a.N % 8 == 0) {
-      *(uint32_t*)(keep + idx * 8) = lo;
-      *(uint32_t*)(keep + idx * 8 + 4) = hi;
-    } else {   // rows of N bytes are not 4-byte aligned, and the last group of a row is partial
-      uint8_t* dst = keep + ((int64_t)bh * a.N + i) * a.N + 8 * (int64_t)g8;
-      const int n = min(8, a.N - 8 * (int)g8);
+      for (int q = 0; q < 4; ++q) {   // four flag bytes at a time
+        const uint32_t nib = (m >> (4 * q)) & 0xFu;
+        *(uint32_t*)(dst + 4 * q) = (nib & 1u) | ((nib & 2u) << 7) | ((nib & 4u) << 14) | ((nib & 8u) << 21);
+      }
+    } else {   // rows of N bytes are not 4-byte aligned, or the last group of a row is partial
       for (int f = 0; f < n; ++f) dst[f] = (uint8_t)((m >> f) & 1u);
     }
   }
@@ -382,7 +383,7 @@ int launch_fwd(const KArgs& a, int dtype, int d, bool causal, bool dropout, bool
 }
 
 int launch_dropout_mask(const KArgs& a, uint8_t* keep, hipStream_t s) {
-  const int64_t total = (int64_t)a.B * a.H * a.N * ((a.N + 7) / 8);
+  const int64_t total = (int64_t)a.B * a.H * a.N * ((a.N + 15) / 16);
   const int blocks = (int)((total + 255) / 256 < 65536 ? (total + 255) / 256 : 65536);
   hipLaunchKernelGGL(dropout_mask_kernel, dim3(blocks), dim3(256), 0, s, a, keep);
   return (int)hipGetLastError();

@@ -202,14 +202,16 @@ __device__ __forceinline__ void fwd_pp_rows(const KArgs& a, const int bh, const 
         part[cc] = sum8(all, 0.f);
       }
       lr_run += (part[0] + part[1]) + (part[2] + part[3]);
-      const KeepLQ kq = keep_tile_lane_query(k0, qi, bh, g, a.offset_lo, a.seed_lo, a.seed_hi, a.drop_thr);
+      const KeepLQ kq = keep_tile_lane_query(k0, qi, bh, g, a.offset_lo, a.seed_lo, a.seed_hi);
+      const uint32_t carry2 = dropout_carry2(a.drop_thr);
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int i4 = 0; i4 < 4; ++i4)
+        for (int i4 = 0; i4 < 4; ++i4) {
+          const Keep4 k4 = keep4(kq.w[kb][i4], carry2);
 #pragma unroll
-          for (int e = 0; e < 4; ++e)
-            if ((((i4 & 1) ? kq.odd : kq.even) >> (8 * (2 * kb + (i4 >> 1)) + e) & 1u) == 0) s[kb][4 * i4 + e] = 0.f;
+          for (int e = 0; e < 4; ++e) s[kb][4 * i4 + e] = keep_or_zero(s[kb][4 * i4 + e], keep_mask(k4, e));
+        }
     }
 #pragma unroll
     for (int cc = 0; cc < 4; ++cc)
