@@ -476,13 +476,17 @@ int choose_dkv(const KArgs& a, int d, bool causal, bool dropout, bool sparse) {
   // planning and the finish kernel).
   // (head dimension 16 exists in that kernel only)
   if (d <= 64 && (!force_role_split() || a.dvalid < d)) return kDkvOneWave;
-  // d = 128, dense, no dropout: the one-wavefront kernel with the V block in LDS (attn_bwd_dkv_fr128.hip)
-  // (with 64 keys per wavefront where a head has at least two blocks of 256 keys and whole 32-query tiles: attn_bwd_dkv_w64.hip)
-  if (!sparse && d == 128 && !dropout && !force_role_split()) {
+  // d = 128, dense: the one-wavefront kernel with the V block in LDS (attn_bwd_dkv_fr128.hip)
+  // (without dropout, with 64 keys per wavefront where a head has at least two blocks of 256 keys
+  // and whole 32-query tiles: attn_bwd_dkv_w64.hip)
+  // (dropout under the causal mask keeps the role-split kernel: measured 15 % faster than the
+  // one-wavefront kernel at B H = 64, N = 1024 and equal at N = 4096; without a mask the
+  // one-wavefront kernel is 1-6 % faster with dropout as well)
+  if (!sparse && d == 128 && !force_role_split() && !(dropout && causal && dkv_variant() == 0)) {
     // measured against the 32-key kernel: 1 % faster at N = 2048, 5 % at 4096, 7 % at 16384; slower below,
     // and slower under the causal mask at every length (its 256-key work items balance worse)
     const bool w64 = dkv_variant() == 3 || (dkv_variant() == 0 && !causal && a.N >= 2048);
-    return w64 && a.N >= 512 && a.N % 32 == 0 ? kDkvOneWave64 : kDkvOneWave128;
+    return w64 && !dropout && a.N >= 512 && a.N % 32 == 0 ? kDkvOneWave64 : kDkvOneWave128;
   }
   return kDkvRoleSplit;
 }
@@ -491,7 +495,7 @@ int launch_dkv_rs(const KArgs& a, int dtype, int d, bool causal, bool dropout, b
   const int choice = choose_dkv(a, d, causal, dropout, sparse);
   if (!sparse && choice == kDkvOneWave) return launch_dkv_fr(a, dtype, d, causal, dropout, false, 0, s);
   if (choice == kDkvOneWave64) return launch_dkv_w64(a, dtype, causal, s);
-  if (choice == kDkvOneWave128) return launch_dkv_fr128(a, dtype, causal, s);
+  if (choice == kDkvOneWave128) return launch_dkv_fr128(a, dtype, causal, dropout, s);
   if (dtype == 0 && d == 32) return launch_td<_Float16, 32>(a, causal, dropout, sparse, s);
   if (dtype == 1 && d == 32) return launch_td<__bf16, 32>(a, causal, dropout, sparse, s);
   if (dtype == 0 && d == 64) return launch_td<_Float16, 64>(a, causal, dropout, sparse, s);

@@ -1,4 +1,4 @@
-// dK / dV kernel for head dimension 128, dense problems without dropout, in which one wavefront
+// dK / dV kernel for head dimension 128, dense problems, in which one wavefront
 // does all four tile products of its 32 keys (the arrangement of
 // attn_bwd_dkv_fr.hip carried to d = 128).
 //
@@ -12,8 +12,11 @@
 // streams, so that consecutive instructions write different accumulators.  Measured 6 % faster
 // than the role-split kernel of attn_bwd_dkv.hip at N = 4096 and 10 % at N = 1024.  Under the causal
 // mask a workgroup takes one key block (not a pair: the loop over a pair costs registers this
-// kernel does not have) and the blocks are dealt out heaviest first.  Dropout is not implemented:
-// those problems keep the role-split kernel.
+// kernel does not have) and the blocks are dealt out heaviest first.  Dropout: a call of the
+// generator decides 16 consecutive keys of a query, i.e. the 16 lanes of one row of the wavefront,
+// which need the draws of the tile's 16 queries 8 i4 + 4 g + e: every lane draws one of them, packs
+// the keep bits and the row exchanges them (draw_keep_lane_key / keep_words_lane_key in
+// attn_common.h, here with 32-query tiles: one call per lane and tile).
 #include <type_traits>
 
 #include "attn_common.h"
@@ -26,7 +29,7 @@ constexpr int NT = 256;
 constexpr int QT = 32;    // queries per streamed tile
 constexpr int D = 128;
 
-template <typename T, bool CAUSAL>
+template <typename T, bool CAUSAL, bool DROPOUT>
 __global__ __launch_bounds__(NT, 2) void dkv_fr128_kernel(const KArgs a) {
   typedef typename Vec<T>::x8 T8;
   constexpr int KK = D / 16, DB = D / 32;
@@ -137,7 +140,9 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr128_kernel(const KArgs a) {
         for (int f = 0; f < PF2; ++f) { rq[f] = qfrag(f); rg[f] = gfrag(f); rv[f] = vfrag(f); }
 #pragma unroll
         for (int i4 = 0; i4 < 4; ++i4) {
-          const f32x4 c4 = *(const f32x4*)(Ds0 + 64 * buf + 8 * i4 + 4 * g);
+          // (with dropout -D joins after the mask: the product starts from zero)
+          f32x4 c4 = {0.f, 0.f, 0.f, 0.f};
+          if constexpr (!DROPOUT) c4 = *(const f32x4*)(Ds0 + 64 * buf + 8 * i4 + 4 * g);
 #pragma unroll
           for (int e = 0; e < 4; ++e) { dp[4 * i4 + e] = c4[e]; s[4 * i4 + e] = 0.f; }
         }
@@ -156,24 +161,40 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr128_kernel(const KArgs a) {
         for (int i = 0; i < 16; ++i)
           if (kj >= len) s[i] = -INFINITY;
       }
-      T8 pf[2];
+      // dropout: this lane draws the tile's query 8 (u / 4) + 4 g + u % 4 (u = r % 16) for the 16 keys
+      // of its row; bit u' of the word of lane u is key u' of that query
+      uint32_t drawn = 0;
+      if constexpr (DROPOUT) {
+        const int u = r & 15;
+        const u32x4 w = philox_draw16((uint32_t)kj >> 4, (uint32_t)(i0 + 8 * (u >> 2) + 4 * g + (u & 3)), (uint32_t)bh,
+                                      a.offset_lo, a.seed_lo, a.seed_hi);
+        drawn = keep_bits16(w, dropout_carry2(a.drop_thr));
+      }
+      T8 pf[2], dsf[2];
 #pragma unroll
       for (int i4 = 0; i4 < 4; ++i4) {
         const f32x4 l4 = *(const f32x4*)(Ls0 + 64 * buf + 8 * i4 + 4 * g);
+        KeepLK4 kw = {};
+        f32x4 d4 = {0.f, 0.f, 0.f, 0.f};
+        if constexpr (DROPOUT) {
+          kw = keep_words_lane_key(drawn, i4);
+          d4 = *(const f32x4*)(Ds0 + 64 * buf + 8 * i4 + 4 * g);   // -D_i
+        }
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int i = 4 * i4 + e;
           float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], c, -l4[e]));
           if (CAUSAL && 8 * i4 + e < hidden_below) p = 0.f;
-          s[i] = p;
-          pf[i4 >> 1][4 * (i4 & 1) + e] = (T)p;
+          if constexpr (DROPOUT) {
+            const uint32_t mask = keep_mask_lane_key(kw.w[e], r & 15);
+            pf[i4 >> 1][4 * (i4 & 1) + e] = (T)keep_or_zero(p, mask);
+            dsf[i4 >> 1][4 * (i4 & 1) + e] = (T)(p * (keep_or_zero(dp[i] * a.keep_scale, mask) + d4[e]));
+          } else {
+            pf[i4 >> 1][4 * (i4 & 1) + e] = (T)p;
+            dsf[i4 >> 1][4 * (i4 & 1) + e] = (T)(p * dp[i]);
+          }
         }
       }
-      T8 dsf[2];
-#pragma unroll
-      for (int i4 = 0; i4 < 4; ++i4)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) dsf[i4 >> 1][4 * (i4 & 1) + e] = (T)(s[4 * i4 + e] * dp[4 * i4 + e]);
       // ---- dV^T += dO^T P and dK^T += Q^T dS (contractions over the 32 queries), alternating
       {
         auto gtr = [&](int f) {   // f = DB cc + db
@@ -209,14 +230,15 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr128_kernel(const KArgs a) {
   {
     // 4 wavefronts x 32 rows x 128 = 32 KB per gradient: the V block, then the four tile buffers
     T* stage_v = Vb + wave * 32 * D;
-    store_rows_coalesced<T, D>(stage_v, (T*)a.dV + head_off + (int64_t)kw0 * a.sn, a.sn, dv, 1.f, a.N - kw0);
+    store_rows_coalesced<T, D>(stage_v, (T*)a.dV + head_off + (int64_t)kw0 * a.sn, a.sn, dv,
+                               DROPOUT ? a.keep_scale : 1.f, a.N - kw0);
     __builtin_amdgcn_wave_barrier();
     store_rows_coalesced<T, D>(stage_v, (T*)a.dK + head_off + (int64_t)kw0 * a.sn, a.sn, dk, a.tau, a.N - kw0);
   }
 }
 
 template <typename T>
-int launch_t(const KArgs& a_in, bool causal, hipStream_t s) {
+int launch_t(const KArgs& a_in, bool causal, bool dropout, hipStream_t s) {
   KArgs a = a_in;
   {
     const int64_t tile_bytes = 2 * (int64_t)a.N * D * (int64_t)sizeof(T);   // Q and dO of one head
@@ -224,15 +246,17 @@ int launch_t(const KArgs& a_in, bool causal, hipStream_t s) {
     a.group = (int)(fit < 1 ? 1 : (fit > 8 ? 8 : fit));
   }
   const dim3 grid(kXcds * a.chunk), block(NT);
-  if (causal) hipLaunchKernelGGL((dkv_fr128_kernel<T, true>), grid, block, 0, s, a);
-  else hipLaunchKernelGGL((dkv_fr128_kernel<T, false>), grid, block, 0, s, a);
+  if (causal && dropout) hipLaunchKernelGGL((dkv_fr128_kernel<T, true, true>), grid, block, 0, s, a);
+  else if (causal) hipLaunchKernelGGL((dkv_fr128_kernel<T, true, false>), grid, block, 0, s, a);
+  else if (dropout) hipLaunchKernelGGL((dkv_fr128_kernel<T, false, true>), grid, block, 0, s, a);
+  else hipLaunchKernelGGL((dkv_fr128_kernel<T, false, false>), grid, block, 0, s, a);
   return (int)hipGetLastError();
 }
 
 }  // namespace
 
-int launch_dkv_fr128(const KArgs& a, int dtype, bool causal, hipStream_t s) {
-  return dtype == 0 ? launch_t<_Float16>(a, causal, s) : launch_t<__bf16>(a, causal, s);
+int launch_dkv_fr128(const KArgs& a, int dtype, bool causal, bool dropout, hipStream_t s) {
+  return dtype == 0 ? launch_t<_Float16>(a, causal, dropout, s) : launch_t<__bf16>(a, causal, dropout, s);
 }
 
 }  // namespace attn

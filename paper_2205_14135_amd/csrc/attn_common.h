@@ -79,8 +79,8 @@ int launch_dkv_rs(const KArgs& a, int dtype, int d, bool causal, bool dropout, b
 // dense dK/dV kernel for d <= 64: one wavefront does all four tile products (attn_bwd_dkv_fr.hip)
 int launch_dkv_fr(const KArgs& a, int dtype, int d, bool causal, bool dropout, bool sparse, int extra_groups,
                   hipStream_t s);
-// the same at d = 128 for dense problems without causal mask and dropout (attn_bwd_dkv_fr128.hip)
-int launch_dkv_fr128(const KArgs& a, int dtype, bool causal, hipStream_t s);
+// the same at d = 128 for dense problems (attn_bwd_dkv_fr128.hip)
+int launch_dkv_fr128(const KArgs& a, int dtype, bool causal, bool dropout, hipStream_t s);
 // the same with 64 keys per wavefront and the accumulators in the accumulation registers (attn_bwd_dkv_w64.hip)
 int launch_dkv_w64(const KArgs& a, int dtype, bool causal, hipStream_t s);
 // dense forward with two wavefront groups in ping-pong (attn_fwd_pp.hip); sets its own work items

@@ -108,7 +108,9 @@ def test_blocksparse_random_per_head_mask_causal_dropout_and_empty_rows():
 
 def test_blocksparse_all_ones_equals_dense():
     """An all-ones block mask is the dense problem.  The dense call may take a different kernel
-    (other summation order), so O is compared to one output ulp and the gradients to 2^-7 relative."""
+    (other summation order, other roundings of P and dS to 16 bits), so O is compared to one output ulp
+    and the gradients by relative L2 distance: each is within 2.6e-3 of the exact gradient (the oracle
+    tests), so the two are within 5e-3 of each other."""
     T = 3
     t, dev = hp.make_case(1, 2, 128 * T, 128, "bf16", 700)
     kw = dict(softmax_scale=0.09, causal=True, dropout_p=0.1, seed=4)
@@ -121,4 +123,4 @@ def test_blocksparse_all_ones_equals_dense():
     assert (L - Ls).abs().max().item() <= 1e-5
     assert ((O.float() - Os.float()).abs() <= 2.0 ** -7 * O.float().abs().clamp_min(2.0 ** -7)).all()
     for a, b in zip(g, gs):
-        assert ((a.float() - b.float()).abs() <= 2.0 ** -6 * b.float().abs().clamp_min(1e-2)).all()
+        assert float((a.float() - b.float()).norm() / b.float().norm()) <= 5e-3

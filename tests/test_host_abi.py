@@ -166,8 +166,9 @@ def test_kernel_choice_query(lib):
     choice = lambda sparse=False, **kw: binding.attn_debug_kernel_choice(_params(**kw), sparse)
     assert choice(B=4, H=16, N=4096, d=128) == ("fwd_pp_kernel", "dkv_w64_kernel")
     assert choice(B=4, H=16, N=4096, d=128, causal=1) == ("fwd_pp_kernel", "dkv_fr128_kernel")
-    assert choice(B=4, H=16, N=4096, d=128, dropout_p=0.1) == ("fwd_kernel", "dkv_rs_kernel")
+    assert choice(B=4, H=16, N=4096, d=128, dropout_p=0.1) == ("fwd_kernel", "dkv_fr128_kernel")
     assert choice(B=8, H=8, N=1024, d=128, causal=1, dropout_p=0.1) == ("fwd_kernel", "dkv_rs_kernel")   # 128 work items only
+    assert choice(B=4, H=16, N=4096, d=128, dropout_p=0.003) == ("fwd_pp_kernel", "dkv_w64_kernel")       # rounds down to no dropout
     assert choice(B=16, H=16, N=512, d=64, dropout_p=0.1) == ("fwd_kernel", "dkv_fr_kernel")
     assert choice(B=1, H=8, N=16384, d=64, sparse=True) == ("fwd_kernel", "dkv_fr_kernel")
     assert choice(B=4, H=16, N=4096, d=128, sparse=True) == ("fwd_kernel", "dkv_rs_kernel")
