@@ -48,9 +48,10 @@ def fwd_variant(request):
 @pytest.fixture
 def dkv_variant(request):
     from paper_2205_14135_amd import binding
-    # (d = 128 with dropout takes the role-split kernel anyway; "fr" keeps the 64-keys-per-wavefront
-    # kernel of d = 128 out and "w64" brings it in wherever it exists, so that both one-wavefront
-    # kernels are reached at every length and under the causal mask)
+    # ("fr" keeps the 64-keys-per-wavefront kernel of d = 128 out and takes the 32-key one also with
+    # the causal mask and dropout together, which "auto" leaves to the role-split kernel; "w64" brings
+    # the 64-key kernel in wherever it exists, so that both one-wavefront kernels are reached at every
+    # length and under the causal mask)
     binding.attn_debug_set_variant(dkv={"role_split": "rs", "one_wave_32_keys": "fr", "one_wave_64_keys": "w64"}.get(request.param, "auto"))
     yield request.param
     binding.attn_debug_set_variant(dkv="auto")

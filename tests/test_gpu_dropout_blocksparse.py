@@ -34,21 +34,113 @@ def test_forward_with_dropout(dtype, d, causal):
     hp.assert_forward_ok(res)
 
 
-def test_kernels_apply_exactly_the_oracle_mask():
-    """Q = 0 makes P uniform, so O_i = (1/((1-p) N)) * sum_{j kept} V_j: with V the N x N identity
-    split over d-wide column slabs, O read back slab by slab IS the keep mask of the kernel."""
-    B, H, N, d, p = 1, 2, 128, 64, 0.3
-    seed, offset = 77, 5
-    Q = torch.zeros((B, H, N, d), dtype=torch.float16, device="cuda")
-    K = torch.zeros_like(Q)
+@pytest.mark.parametrize("name", ["C2", "C3", "C3_d128"])
+def test_dropout_mask_every_bit_at_benchmark_shapes(name):
+    """The whole [B, H, N, N] keep mask of the dropout benchmark shapes (seed and offset as bench.py
+    uses them), every bit against the oracle."""
+    c = inputs.CONFIGS[name]
+    B, H, N, p = c["B"], c["H"], c["N"], c["p_drop"]
+    seed, offset = inputs.BASE_DROPOUT_SEED, 0
+    keep = binding.attn_debug_dropout_mask(B, H, N, p, seed, offset)
+    kept = 0
+    for b in range(B):
+        got = keep[b].cpu().numpy().astype(bool)
+        for h in range(H):
+            want = orc.dropout_keep_mask(b, h, H, N, p, seed, offset)
+            assert (got[h] == want).all(), (b, h)
+            kept += int(want.sum())
+    frac = kept / (B * H * N * N)
+    assert abs(frac - (1 - orc.dropout_effective_p(p))) < 1e-3, frac
+
+
+def _want_masks(H, N, p, seed, offset, causal):
     want = np.stack([orc.dropout_keep_mask(0, h, H, N, p, seed, offset) for h in range(H)])
-    got = np.zeros((H, N, N), dtype=bool)
-    for slab in range(N // d):
-        V = torch.zeros((B, H, N, d), dtype=torch.float16, device="cuda")
+    return want & np.tril(np.ones((N, N), dtype=bool)) if causal else want
+
+
+@pytest.mark.parametrize("d,N,causal,variant", [
+    (64, 128, False, "auto"), (64, 256, True, "pp"), (128, 512, False, "pp"), (128, 512, True, "pp"),
+    (128, 384, True, "auto"), (32, 128, False, "auto"), (16, 128, True, "auto"),
+])
+def test_forward_kernels_apply_exactly_the_oracle_mask(d, N, causal, variant):
+    """Q = K = 0 makes P uniform over the visible keys, so O_i = (scale / n_i) * sum_{j kept} V_j: with
+    V the N x N identity split over d-wide column slabs, O read back slab by slab IS the mask the
+    kernel applied (kept and visible entries are positive, all others exactly zero)."""
+    B, H, p = 1, 2, 0.3
+    seed, offset = 77, 5
+    binding.attn_debug_set_variant(fwd=variant)
+    try:
+        Q = torch.zeros((B, H, N, d), dtype=torch.float16, device="cuda")
+        K = torch.zeros_like(Q)
+        got = np.zeros((H, N, N), dtype=bool)
         idx = torch.arange(d, device="cuda")
+        for slab in range(N // d):
+            V = torch.zeros((B, H, N, d), dtype=torch.float16, device="cuda")
+            V[:, :, slab * d + idx, idx] = 1.0
+            O, _ = binding.attn_fwd(Q, K, V, softmax_scale=1.0, causal=causal, dropout_p=p, seed=seed,
+                                    offset=offset, o_fp32=True)
+            assert (O >= 0).all()
+            got[:, :, slab * d:(slab + 1) * d] = (O[0] > 0).cpu().numpy()
+    finally:
+        binding.attn_debug_set_variant(fwd="auto")
+    assert (got == _want_masks(H, N, p, seed, offset, causal)).all()
+
+
+@pytest.mark.parametrize("variant", ["auto", "rs", "fr"])
+@pytest.mark.parametrize("d,N,causal", [(64, 512, False), (64, 576, True), (128, 512, False), (128, 640, True),
+                                        (32, 256, True)])
+def test_backward_kernels_apply_exactly_the_oracle_mask(d, N, causal, variant):
+    """The same read-back for the dK/dV kernels: with Q = K = 0 and dO the N x N identity split over
+    d-wide column slabs, dV_j = sum_i Z_ij P_ij dO_i has dV[j, c] = Z_ij scale / n_i for query
+    i = slab * d + c, so dV read back slab by slab is the (transposed) mask the kernel regenerated
+    (Appendix B.4, observation 1: the backward pass redraws the forward's mask from the saved state).
+    dQ and dK must come out as exact zeros (K = 0 and Q = 0)."""
+    B, H, p = 1, 2, 0.3
+    seed, offset = 1234567, 0x2_0000_0001
+    kw = dict(softmax_scale=1.0, causal=causal, dropout_p=p, seed=seed, offset=offset)
+    binding.attn_debug_set_variant(dkv=variant)
+    try:
+        Q = torch.zeros((B, H, N, d), dtype=torch.bfloat16, device="cuda")
+        K, V = torch.zeros_like(Q), torch.zeros_like(Q)
+        O, L = binding.attn_fwd(Q, K, V, **kw)
+        got = np.zeros((H, N, N), dtype=bool)
+        idx = torch.arange(d, device="cuda")
+        for slab in range(N // d):
+            dO = torch.zeros_like(Q)
+            dO[:, :, slab * d + idx, idx] = 1.0
+            dQ, dK, dV = binding.attn_bwd(Q, K, V, O, dO, L, **kw)
+            assert (dV >= 0).all() and not dQ.any() and not dK.any()
+            got[:, slab * d:(slab + 1) * d, :] = (dV[0] > 0).cpu().numpy().transpose(0, 2, 1)
+    finally:
+        binding.attn_debug_set_variant(dkv="auto")
+    assert (got == _want_masks(H, N, p, seed, offset, causal)).all()
+
+
+def test_dispatcher_takes_the_two_group_forward_with_causal_mask_and_dropout():
+    """d = 128 with at least 256 paired work items: the library's own choice is the two-group forward,
+    here with the causal mask and dropout at a full-size shape (B=4, H=16, N=2048), against the oracle
+    on whole heads and through the V-identity read-back of the applied mask for one head."""
+    B, H, N, d, p = 4, 16, 2048, 128, 0.1
+    seed = inputs.BASE_DROPOUT_SEED + 5
+    t, dev = hp.make_case(B, H, N, d, "bf16", 470)
+    prm = binding.make_params(dev["Q"], 1 / math.sqrt(d), causal=True, dropout_p=p, seed=seed)
+    assert binding.attn_debug_kernel_choice(prm, sparse=False)[0] == "fwd_pp_kernel"
+    heads = [(0, 0), (3, 15)]
+    res = hp.check_forward(t, dev, "bf16", 1 / math.sqrt(d), causal=True, p=p, seed=seed, heads=heads)
+    print("pp by dispatcher fwd", res)
+    hp.assert_forward_ok(res)
+    resb = hp.check_backward(t, dev, "bf16", 1 / math.sqrt(d), causal=True, p=p, seed=seed, heads=heads)
+    print("pp by dispatcher bwd", resb)
+    hp.assert_backward_ok(resb)
+    Q = torch.zeros((B, H, N, d), dtype=torch.bfloat16, device="cuda")
+    got = np.zeros((N, N), dtype=bool)
+    idx = torch.arange(d, device="cuda")
+    for slab in range(N // d):
+        V = torch.zeros_like(Q)
         V[:, :, slab * d + idx, idx] = 1.0
-        O, _ = binding.attn_fwd(Q, K, V, softmax_scale=1.0, dropout_p=p, seed=seed, offset=offset, o_fp32=True)
-        got[:, :, slab * d:(slab + 1) * d] = (O[0] > 0).cpu().numpy()
+        O, _ = binding.attn_fwd(Q, Q, V, softmax_scale=1.0, causal=True, dropout_p=p, seed=seed, o_fp32=True)
+        got[:, slab * d:(slab + 1) * d] = (O[2, 7] > 0).cpu().numpy()
+    want = orc.dropout_keep_mask(2, 7, H, N, p, seed, 0) & np.tril(np.ones((N, N), dtype=bool))
     assert (got == want).all()
 
 
