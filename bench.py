@@ -252,6 +252,26 @@ def sparsity_sweep(steps):
               file=sys.stderr, flush=True)
 
 
+def dropout_cost(wl, steps, warmup):
+    """Each dropout workload with its dropout and with p = 0 at the same shape: per-kernel times and their
+    ratios (Appendix E.6 of the paper tabulates the same pair of settings)."""
+    from paper_2205_14135_amd import inputs
+    for name in ("bert_large", "gpt2_medium", "gpt2_medium_d128"):
+        c = wl[name]
+        with_p = run_gpu(c, steps, warmup, inputs.BASE_SEED + 3)
+        without = run_gpu(dict(c, p=0.0), steps, warmup, inputs.BASE_SEED + 3)
+        k1 = [with_p["kernel_ms"][n] for n in with_p["names"]]
+        k0 = [without["kernel_ms"][n] for n in without["names"]]
+        line = dict(workload=name, p=c["p"], kernels=with_p["names"], kernels_without=without["names"],
+                    ms=[round(x, 4) for x in k1], ms_without=[round(x, 4) for x in k0],
+                    ratio=[round(a / b, 3) for a, b in zip(k1, k0)],
+                    fwd_ratio=round(k1[0] / k0[0], 3), bwd_ratio=round(sum(k1[1:]) / sum(k0[1:]), 3),
+                    step_ratio=round(sum(k1) / sum(k0), 3),
+                    ms_per_step=round(with_p["ms_per_step"], 4), ms_per_step_without=round(without["ms_per_step"], 4),
+                    wall_ratio=round(with_p["ms_per_step"] / without["ms_per_step"], 3))
+        print(json.dumps(line), file=sys.stderr, flush=True)
+
+
 def memory_and_naive(steps):
     """Device memory and time of this library against a plain materialise-S attention written with
     PyTorch ops (Algorithm 0 of the paper: S = QK^T, P = softmax(S), O = PV, autograd backward),
@@ -418,6 +438,10 @@ def main():
     ap.add_argument("--naive-steps", type=int, default=0,
                     help="only: run this many forward+backward steps of a materialise-S attention in PyTorch ops at the "
                          "workload's shape (comparison system for the HBM byte counters)")
+    ap.add_argument("--dropout-p", type=float, default=None,
+                    help="override the workload's dropout probability (0 switches dropout off at the same shape)")
+    ap.add_argument("--dropout-cost", action="store_true",
+                    help="only: the three dropout workloads timed with their dropout and with none (JSON lines on stderr)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a 1 GiB elementwise copy kernel (reference for the HBM byte counters)")
     args = ap.parse_args()
@@ -447,8 +471,14 @@ def main():
         return
     from paper_2205_14135_amd import binding, inputs
     binding.load()
+    if args.dropout_p is not None:
+        for c in wl.values():
+            c["p"] = args.dropout_p
     if args.sparsity_sweep:
         sparsity_sweep(max(3, args.steps // 3))
+        return
+    if args.dropout_cost:
+        dropout_cost(wl, args.steps, args.warmup)
         return
     if args.memory_table:
         memory_and_naive(max(3, args.steps // 3))

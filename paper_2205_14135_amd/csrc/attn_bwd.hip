@@ -225,20 +225,18 @@ __global__ __launch_bounds__(NT, 2) void dq_kernel(const KArgs a) {
       // P = exp(S - L); dS = P o (dP o Z - D)
       KeepLQ kq = {};
       if constexpr (DROPOUT) kq = keep_tile_lane_query(k0, qi, bh, g, a.offset_lo, a.seed_lo, a.seed_hi);
-      const uint32_t carry2 = dropout_carry2(a.drop_thr);
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int i4 = 0; i4 < 4; ++i4) {
-          Keep4 k4 = {};
-          if constexpr (DROPOUT) k4 = keep4(kq.w[kb][i4], carry2);
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             const int i = 4 * i4 + e;
             float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][i], c, -l2));
             if (CAUSAL && k0 + 32 * kb + 8 * i4 + 4 * g + e > qi) p = 0.f;
             float dpv = dp[kb][i];
-            if constexpr (DROPOUT) dpv = keep_or_zero(dpv * a.keep_scale, keep_mask(k4, e)) + neg_d;
+            if constexpr (DROPOUT)   // Z dP - D with Z = keep_scale or 0 by the 8-bit draw of this element
+              dpv = dropped(kq.w[kb][i4], e, a.drop_thr) ? neg_d : __builtin_fmaf(dpv, a.keep_scale, neg_d);
             s[kb][i] = p * dpv;
           }
         }

@@ -45,7 +45,7 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
   // and anything below 2^-24 contributes nothing to dS), because role B can multiply an fp16 half
   // by an fp32 value in one mixed-precision instruction, with no unpacking
   __shared__ __attribute__((aligned(16))) f16x8 Px[2][4][4][64];
-  __shared__ uint32_t Kw[2][4][64];                                // dropout keep words [buf][pair][lane]
+  __shared__ __attribute__((aligned(16))) uint32_t Kw[2][4][64];                                // dropout keep words [buf][pair][lane]
 
   const int n_kt = a.T;   // ceil(N / 128): the last key block may be ragged
   // Work assignment.  Dense: one key block per workgroup; under the causal mask key block k is
@@ -204,7 +204,6 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
   };
   // Dropout bits in this layout: see draw_keep_lane_key() / keep_words_lane_key() in attn_common.h.
   const int kbit = r & 15;   // position of this lane's key in the 16-key group of a draw
-  auto keep_words = [&](uint32_t mine, KeepLK& kw) { kw = keep_words_lane_key(mine); };
   auto draw_keep = [&](int i0) {
     return draw_keep_lane_key(i0, kj, r, g, bh, a.offset_lo, a.seed_lo, a.seed_hi, a.drop_thr);
   };
@@ -214,9 +213,10 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
     row_product(Qs[q4], false, nullptr);                         // S = Q K^T
     KeepLK kw = {};
     if constexpr (DROPOUT) {
-      const uint32_t mine = draw_keep(i0);
-      Kw[p2][pair][lane] = mine;   // role B regenerates nothing: it reads the drawn bits
-      keep_words(mine, kw);
+      // the drawn bits go to LDS: the lanes of a 16-lane row read each other's words there, and
+      // role B regenerates nothing, it reads them too
+      keep_row_store(Kw[p2][pair], draw_keep(i0));
+      kw = keep_row_load_all(Kw[p2][pair]);
     }
     if (kw0 + 32 > len) {   // this wavefront holds padded keys: their logits become -inf, hence P = 0
 #pragma unroll
@@ -253,7 +253,7 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
   // ---- role B, second half for the previous tile: dS from sd (= dP) and A's P, then dK
   auto role_b_ds_dk = [&](int q4, int p2) {
     KeepLK kw = {};
-    if constexpr (DROPOUT) keep_words(Kw[p2][pair][lane], kw);
+    if constexpr (DROPOUT) kw = keep_row_load_all(Kw[p2][pair]);
     f16x8 pin[4];
     T8 dsf[4];
 #pragma unroll
@@ -270,7 +270,7 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
           const int cc = 2 * qb + (i4 >> 1), t = 4 * (i4 & 1) + e;
           float dpv = sd[qb][i];   // without dropout: already dP - D
           if constexpr (DROPOUT) {
-            dpv = keep_or_zero(dpv * a.keep_scale, keep_mask_lane_key(kw.w[i4][e], kbit + 16 * qb)) + d4[e];
+            dpv = dropped_dp_minus_d(dpv, a.keep_scale, keep_mask_lane_key(kw.w[i4][e], kbit + 16 * qb), d4[e]);
           }
           // (an fma with an fp16 operand is one v_fma_mix_f32: the half is widened inside the instruction)
           dsf[cc][t] = (T)__builtin_fmaf((float)pin[cc][t], dpv, 0.f);

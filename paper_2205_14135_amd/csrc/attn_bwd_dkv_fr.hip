@@ -49,6 +49,11 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr_kernel(const KArgs a) {
     __shared__ __attribute__((aligned(16))) float Ds[2 * TILE];
     Qs0 = Qs; Gs0 = Gs; Ls0 = Ls; Ds0 = Ds;
   }
+  // dropout: the keep bits are exchanged along 16-lane rows either through one 64-word LDS slot per
+  // wavefront (four 16-byte reads per pass) or by row broadcasts (sixteen per pass, no memory); the
+  // forms that are short of registers keep the broadcasts, whose results need no aligned quadruples
+  constexpr bool ROW_LDS = DROPOUT && !CAUSAL && !SPARSE;
+  __shared__ __attribute__((aligned(16))) uint32_t Kb[ROW_LDS ? NT / 64 : 1][64];
 
   const int n_kt = a.T;   // ceil(N / 128): the last key block may be ragged
   // Work assignment.  Dense: one key block per workgroup; under the causal mask key block k is
@@ -229,8 +234,11 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr_kernel(const KArgs a) {
     if (!CAUSAL || i0 + TILE - 1 >= kw0) {
       f32x16 s[2], dp[2];
       row_product(Qs0 + buf * TILE * D, kf, false, nullptr, s);                // S = Q K^T
-      uint32_t drawn = 0;   // this lane's packed keep bits; the words of a row group are fetched where they are used
+      // this lane's packed keep bits; the words of a row group are fetched where they are used
+      uint32_t drawn = 0;
+      uint32_t* const kslot = Kb[ROW_LDS ? (threadIdx.x >> 6) : 0];
       if constexpr (DROPOUT) drawn = draw_keep(i0);
+      if constexpr (ROW_LDS) keep_row_store(kslot, drawn);
       if (kw0 + 32 > len) {   // this wavefront holds padded keys: their logits become -inf, hence P = 0
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb)
@@ -243,7 +251,8 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr_kernel(const KArgs a) {
 #pragma unroll
       for (int i4 = 0; i4 < 4; ++i4) {
         KeepLK4 kw = {};
-        if constexpr (DROPOUT) kw = keep_words_lane_key(drawn, i4);
+        if constexpr (ROW_LDS) kw = keep_row_load(kslot, i4);
+        else if constexpr (DROPOUT) kw = keep_words_lane_key(drawn, i4);
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
           const f32x4 l4 = *(const f32x4*)(Ls0 + buf * TILE + 32 * qb + 8 * i4 + 4 * g);
@@ -266,14 +275,15 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr_kernel(const KArgs a) {
       // dP = dO V^T; without dropout it starts from -D, so the result is dP - D
       row_product(Gs0 + buf * TILE * D, vf, !DROPOUT, Ds0 + buf * TILE, dp);
       T8 dsf[4];
-      // (the row broadcasts are repeated here rather than kept from the P pass: sixteen registers
-      // held across the dP product would spill; the empty statement keeps the compiler from
-      // merging the two sets)
-      if constexpr (DROPOUT) asm volatile("" : "+v"(drawn));
+      // (the keep words are fetched again here rather than kept from the P pass: sixteen registers
+      // held across the dP product would spill; the empty statement keeps the compiler from merging
+      // the two sets of broadcasts)
+      if constexpr (DROPOUT && !ROW_LDS) asm volatile("" : "+v"(drawn));
 #pragma unroll
       for (int i4 = 0; i4 < 4; ++i4) {
         KeepLK4 kw = {};
-        if constexpr (DROPOUT) kw = keep_words_lane_key(drawn, i4);
+        if constexpr (ROW_LDS) kw = keep_row_load(kslot, i4);
+        else if constexpr (DROPOUT) kw = keep_words_lane_key(drawn, i4);
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
           f32x4 d4 = {0.f, 0.f, 0.f, 0.f};
@@ -284,7 +294,7 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr_kernel(const KArgs a) {
             const int cc = 2 * qb + (i4 >> 1), tt = 4 * (i4 & 1) + e;
             float dpv = dp[qb][i];
             if constexpr (DROPOUT) {
-              dpv = keep_or_zero(dpv * a.keep_scale, keep_mask_lane_key(kw.w[e], kbit + 16 * qb)) + d4[e];
+              dpv = dropped_dp_minus_d(dpv, a.keep_scale, keep_mask_lane_key(kw.w[e], kbit + 16 * qb), d4[e]);
             }
             dsf[cc][tt] = (T)(s[qb][i] * dpv);
           }

@@ -188,7 +188,7 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr128_kernel(const KArgs a) {
           if constexpr (DROPOUT) {
             const uint32_t mask = keep_mask_lane_key(kw.w[e], r & 15);
             pf[i4 >> 1][4 * (i4 & 1) + e] = (T)keep_or_zero(p, mask);
-            dsf[i4 >> 1][4 * (i4 & 1) + e] = (T)(p * (keep_or_zero(dp[i] * a.keep_scale, mask) + d4[e]));
+            dsf[i4 >> 1][4 * (i4 & 1) + e] = (T)(p * dropped_dp_minus_d(dp[i], a.keep_scale, mask, d4[e]));
           } else {
             pf[i4 >> 1][4 * (i4 & 1) + e] = (T)p;
             dsf[i4 >> 1][4 * (i4 & 1) + e] = (T)(p * dp[i]);

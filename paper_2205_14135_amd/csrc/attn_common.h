@@ -174,6 +174,37 @@ __device__ __forceinline__ uint32_t keep_mask(const Keep4& k, int f) {
 __device__ __forceinline__ float keep_or_zero(float x, uint32_t mask) {
   return __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, x) & mask);
 }
+// true when the 8-bit draw in byte e (a constant, 0..3) of the word is below the threshold: the element is dropped
+__device__ __forceinline__ bool dropped(uint32_t w, int e, uint32_t thr8) { return ((w >> (8 * e)) & 0xFFu) < thr8; }
+// Dropout on a fragment of eight packed 16-bit values (four registers; element t in half t % 2 of
+// register t / 2): element t is zeroed when its 8-bit draw, byte t % 4 of word t / 4 (w_lo, w_hi), is
+// below the threshold.  Sub-dword operand addressing does the field extract, the compare and the
+// half-register write in two instructions per element, on the values already rounded to 16 bits.
+// thr8 and zero are registers holding T and 0.  Written out by hand because the compiler has no
+// half-register select; a register written through a sub-dword destination must not be read by the
+// next instruction (one wait state), which the order below keeps (the two halves of a register are
+// eight instructions apart), and the closing s_nop separates the last writes from whatever follows.
+template <typename T8>
+__device__ __forceinline__ void drop_fragment8(T8& frag, uint32_t w_lo, uint32_t w_hi, uint32_t thr8, uint32_t zero) {
+  const u32x4 p = __builtin_bit_cast(u32x4, frag);
+  uint32_t p0 = p[0], p1 = p[1], p2 = p[2], p3 = p[3];
+#define ATTN_DROP_HALF(REG, WORD, BYTE, HALF)                                                       \
+  "v_cmp_lt_u32_sdwa vcc, " WORD ", %6 src0_sel:BYTE_" #BYTE " src1_sel:DWORD\n\t"                   \
+  "v_cndmask_b32_sdwa " REG ", " REG ", %7, vcc dst_sel:WORD_" #HALF                                \
+  " dst_unused:UNUSED_PRESERVE src0_sel:WORD_" #HALF " src1_sel:DWORD\n\t"
+  asm volatile(
+      ATTN_DROP_HALF("%0", "%4", 0, 0) ATTN_DROP_HALF("%1", "%4", 2, 0)
+      ATTN_DROP_HALF("%2", "%5", 0, 0) ATTN_DROP_HALF("%3", "%5", 2, 0)
+      ATTN_DROP_HALF("%0", "%4", 1, 1) ATTN_DROP_HALF("%1", "%4", 3, 1)
+      ATTN_DROP_HALF("%2", "%5", 1, 1) ATTN_DROP_HALF("%3", "%5", 3, 1)
+      "s_nop 1"
+      : "+v"(p0), "+v"(p1), "+v"(p2), "+v"(p3)
+      : "v"(w_lo), "v"(w_hi), "v"(thr8), "v"(zero)
+      : "vcc");
+#undef ATTN_DROP_HALF
+  const u32x4 q = {p0, p1, p2, p3};
+  frag = __builtin_bit_cast(T8, q);
+}
 // the sixteen keep bits of a call: bit f set iff key 16 g16 + f is kept
 __device__ __forceinline__ uint32_t keep_bits16(const u32x4& w, uint32_t carry2) {
   uint32_t bits = 0;
@@ -258,9 +289,35 @@ __device__ __forceinline__ KeepLK keep_words_lane_key(uint32_t mine) {
   k.w[3][2] = row16_broadcast<14>(mine);  k.w[3][3] = row16_broadcast<15>(mine);
   return k;
 }
+// The same exchange through LDS, for kernels that fetch a row group where they use it (they cannot
+// hold all sixteen words): every lane stores its packed word into its wavefront's 64-word slot, and
+// the four words of row group i4 of a lane's 16-lane row are one 16-byte read (all lanes of the row
+// read the same address).  No barrier: one wavefront's LDS instructions execute in order.
+struct KeepLK4 { uint32_t w[4]; };
+__device__ __forceinline__ void keep_row_store(uint32_t* slot64, uint32_t mine) { slot64[threadIdx.x & 63] = mine; }
+__device__ __forceinline__ KeepLK4 keep_row_load(const uint32_t* slot64, int i4) {
+  const u32x4 v = *(const u32x4*)(slot64 + (threadIdx.x & 48) + 4 * i4);
+  KeepLK4 k;
+  k.w[0] = v[0]; k.w[1] = v[1]; k.w[2] = v[2]; k.w[3] = v[3];
+  return k;
+}
+// all sixteen words of the lane's row (row groups i4 = 0..3), for kernels that hold them
+__device__ __forceinline__ KeepLK keep_row_load_all(const uint32_t* slot64) {
+  KeepLK k;
+#pragma unroll
+  for (int i4 = 0; i4 < 4; ++i4) {
+    const u32x4 v = *(const u32x4*)(slot64 + (threadIdx.x & 48) + 4 * i4);
+    k.w[i4][0] = v[0]; k.w[i4][1] = v[1]; k.w[i4][2] = v[2]; k.w[i4][3] = v[3];
+  }
+  return k;
+}
+// Z dP - D for one element: dP times keep_scale where the key was kept (mask all ones), times zero
+// where it was dropped, plus -D, as one multiply-add with a masked factor
+__device__ __forceinline__ float dropped_dp_minus_d(float dp, float keep_scale, uint32_t mask, float neg_d) {
+  return __builtin_fmaf(dp, __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, keep_scale) & mask), neg_d);
+}
 // The four words of row group i4 only (i4 a constant after unrolling), for kernels that cannot
 // afford to hold all sixteen: they fetch a row group where they use it.
-struct KeepLK4 { uint32_t w[4]; };
 __device__ __forceinline__ KeepLK4 keep_words_lane_key(uint32_t mine, int i4) {
   KeepLK4 k;
   switch (i4) {
@@ -274,6 +331,76 @@ __device__ __forceinline__ KeepLK4 keep_words_lane_key(uint32_t mine, int i4) {
 // all ones if this lane's key is kept for query (qb, i4, e); bit = (r % 16) + 16 qb
 __device__ __forceinline__ uint32_t keep_mask_lane_key(uint32_t word, int bit) {
   return (uint32_t)__builtin_amdgcn_sbfe((int)word, bit, 1);
+}
+
+// Online softmax of one 64-key tile in the "lane = query" layout of the forward kernels (Algorithm 2
+// of the paper's follow-up formulation of Algorithm 1's inner loop, base 2): s holds the raw logits
+// S^T (two 32-key blocks; lane (r, g) has query row q0 + r and keys 32 kb + 8 (i / 4) + 4 g + i % 4)
+// and is left holding the unnormalised probabilities; pf receives them rounded to T as the four
+// 16-key B-operand fragments of O^T += V^T P^T, with dropout applied.  Masks keys beyond `last`
+// on tiles that cross the causal diagonal or the end of the sequence, moves the running reference
+// m_run (and rescales o, l_run, lr_run) only when a row of the wavefront outgrew it by more than
+// kLazyRescale, and keeps two row sums per lane: l_run of the exact probabilities (for the saved
+// statistic) and lr_run of the rounded ones (the normaliser of O), both before dropout.
+template <typename T, int DB, bool CAUSAL, bool DROPOUT>
+__device__ __forceinline__ void softmax_tile_lane_query(const KArgs& a, f32x16 (&s)[2], f32x16 (&o)[DB],
+                                                        typename Vec<T>::x8 (&pf)[4], float& m_run, float& l_run,
+                                                        float& lr_run, float c, int k0, int q0, int qi, int len, int g,
+                                                        int bh) {
+  if ((CAUSAL && k0 + 63 > q0) || k0 + 64 > len) {   // diagonal tiles, and the padded last tile
+    const int last = CAUSAL ? min(qi, len - 1) : len - 1;   // last visible key of this row
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int key = k0 + 32 * kb + 8 * (i >> 2) + 4 * g + (i & 3);
+        if (key > last) s[kb][i] = -INFINITY;
+      }
+  }
+  float mx = s[0][0];
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[kb][i]);
+  mx = fmaxf(mx, xchg32(mx)) * c;
+  if (__builtin_amdgcn_ballot_w64(mx > m_run + kLazyRescale) != 0) {   // wavefront-uniform: rare after the first tiles
+    const float m_new = fmaxf(m_run, mx);
+    const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
+    m_run = m_new;
+    l_run *= alpha;
+    lr_run *= alpha;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
+  }
+  const float m_use = (m_run == -INFINITY) ? 0.f : m_run;
+  float psum = 0.f;
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][i], c, -m_use));
+      s[kb][i] = p;
+      psum += p;
+    }
+  l_run += psum;
+  // P^T fragments: 16-key chunk cc = 2 kb + half
+#pragma unroll
+  for (int cc = 0; cc < 4; ++cc)
+#pragma unroll
+    for (int t = 0; t < 8; ++t) pf[cc][t] = (T)s[cc >> 1][8 * (cc & 1) + t];
+  float part[4];
+#pragma unroll
+  for (int cc = 0; cc < 4; ++cc) part[cc] = sum8(pf[cc], 0.f);
+  lr_run += (part[0] + part[1]) + (part[2] + part[3]);
+  if constexpr (DROPOUT) {   // element t of chunk cc has field t % 4 of word 2 (cc & 1) + t / 4 of its block
+    const KeepLQ kq = keep_tile_lane_query(k0, qi, bh, g, a.offset_lo, a.seed_lo, a.seed_hi);
+#pragma unroll
+    for (int cc = 0; cc < 4; ++cc)
+      drop_fragment8(pf[cc], kq.w[cc >> 1][2 * (cc & 1)], kq.w[cc >> 1][2 * (cc & 1) + 1], a.drop_thr, 0u);
+  }
 }
 
 // Work-item index for this workgroup: consecutive items share an XCD (workgroups are

@@ -149,80 +149,7 @@ __device__ __forceinline__ void fwd_pp_rows(const KArgs& a, const int bh, const 
   };
 
   auto do_softmax = [&](int j) {
-    const int k0 = j * BC;
-    if ((CAUSAL && k0 + BC - 1 > q0) || k0 + BC > len) {   // diagonal tiles, and the padded last tile
-      const int last = CAUSAL ? min(qi, len - 1) : len - 1;
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int key = k0 + 32 * kb + 8 * (i >> 2) + 4 * g + (i & 3);
-          if (key > last) s[kb][i] = -INFINITY;
-        }
-    }
-    float mx = s[0][0];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[kb][i]);
-    mx = fmaxf(mx, xchg32(mx)) * c;
-    // move the reference (and rescale O) only when some row of this wavefront outgrew it by more
-    // than kLazyRescale (wavefront-uniform branch): on most tiles nothing is rescaled
-    if (__builtin_amdgcn_ballot_w64(mx > m_run + kLazyRescale) != 0) {
-      const float m_new = fmaxf(m_run, mx);
-      const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
-      m_run = m_new;
-      l_run *= alpha;
-      lr_run *= alpha;
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
-    }
-    const float m_use = (m_run == -INFINITY) ? 0.f : m_run;
-    float psum = 0.f;
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][i], c, -m_use));
-        s[kb][i] = p;
-        psum += p;
-      }
-    l_run += psum;
-    if constexpr (DROPOUT) {
-      // the normaliser sums the rounded probabilities before dropout
-      float part[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int cc = 0; cc < 4; ++cc) {
-        T8 all;
-#pragma unroll
-        for (int t = 0; t < 8; ++t) all[t] = (T)s[cc >> 1][8 * (cc & 1) + t];
-        part[cc] = sum8(all, 0.f);
-      }
-      lr_run += (part[0] + part[1]) + (part[2] + part[3]);
-      const KeepLQ kq = keep_tile_lane_query(k0, qi, bh, g, a.offset_lo, a.seed_lo, a.seed_hi);
-      const uint32_t carry2 = dropout_carry2(a.drop_thr);
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int i4 = 0; i4 < 4; ++i4) {
-          const Keep4 k4 = keep4(kq.w[kb][i4], carry2);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) s[kb][4 * i4 + e] = keep_or_zero(s[kb][4 * i4 + e], keep_mask(k4, e));
-        }
-    }
-#pragma unroll
-    for (int cc = 0; cc < 4; ++cc)
-#pragma unroll
-      for (int t = 0; t < 8; ++t) pf[cc][t] = (T)s[cc >> 1][8 * (cc & 1) + t];
-    if constexpr (!DROPOUT) {
-      float part[4];
-#pragma unroll
-      for (int cc = 0; cc < 4; ++cc) part[cc] = sum8(pf[cc], 0.f);
-      lr_run += (part[0] + part[1]) + (part[2] + part[3]);
-    }
+    softmax_tile_lane_query<T, DB, CAUSAL, DROPOUT>(a, s, o, pf, m_run, l_run, lr_run, c, j * BC, q0, qi, len, g, bh);
   };
 
   // ring slot of a tile in this group's ring
