@@ -55,14 +55,17 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
   // global-token column) alone; those were cut into segments by sparse_plan_kernel and the
   // remaining workgroups walk that segment list.
   const int n_col_groups = kXcds * a.chunk;
-  const bool list_mode = SPARSE && (int)blockIdx.x >= n_col_groups;
+  // (the list workgroups come first in the grid, a multiple of the XCD count of them, so that the
+  // long segments start with the launch instead of queueing behind every column)
+  const int n_list = SPARSE ? (int)gridDim.x - n_col_groups : 0;
+  const bool list_mode = SPARSE && (int)blockIdx.x < n_list;
   constexpr bool PAIRED = CAUSAL && !SPARSE;
   const int n_pair = (n_kt + 1) / 2;
   for (int round = 0;; ++round) {
   int item, skip_blocks = 0, take_blocks = 0x7fffffff;
   bool heavy = false, last_round = true;
   if (!list_mode) {
-    item = xcd_item(a.n_items, a.chunk);
+    item = xcd_item(a.n_items, a.chunk, (int)blockIdx.x - n_list);
     if (item < 0) return;
     if constexpr (SPARSE) {
       if (a.colcnt[item] > a.seglist[2]) return;
@@ -73,7 +76,7 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
       item = (item / n_pair) * n_kt + (round == 0 ? q : n_kt - 1 - q);
     }
   } else {
-    const int idx = ((int)blockIdx.x - n_col_groups) + round * ((int)gridDim.x - n_col_groups);
+    const int idx = (int)blockIdx.x + round * n_list;
     if (idx >= a.seglist[0]) return;
     const int e = a.seglist[kSegHeader + idx];
     item = e / kMaxSegs;
@@ -320,13 +323,14 @@ __global__ __launch_bounds__(NT) void dkv_rs_kernel(const KArgs a) {
 
   const float out_scale = role_b ? a.tau : (DROPOUT ? a.keep_scale : 1.f);
   if (SPARSE && heavy) {
-    // one of several segments of this column: sum in fp32; sparse_finish_kernel converts
-    float* dst = (role_b ? a.dKacc : a.dVacc) + ((int64_t)bh * a.N + kj) * D;
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int i = 0; i < 16; ++i)
-        unsafeAtomicAdd(dst + 32 * db + 8 * (i >> 2) + 4 * g + (i & 3), acc[db][i] * out_scale);
+    // one of several segments of this column: sum in fp32; sparse_finish_kernel converts.  The four
+    // Q buffers stage 32 x D floats for each of four wavefronts: role A's dV first, then role B's dK
+    __syncthreads();   // role B has finished reading the tiles
+    float* stage = (float*)&Qs[0][0] + pair * 32 * D;
+    const int64_t acc_row0 = ((int64_t)bh * a.N + kw0) * D;
+    if (!role_b) atomic_add_rows_coalesced<D>(stage, a.dVacc + acc_row0, acc, out_scale, D == 32 ? a.dvalid : D);
+    __syncthreads();
+    if (role_b) atomic_add_rows_coalesced<D>(stage, a.dKacc + acc_row0, acc, out_scale, D == 32 ? a.dvalid : D);
   } else {
     __syncthreads();   // role B has finished reading the tiles: they stage the output rows
     T* stage = (role_b ? &Gs[0][0] : &Qs[0][0]) + pair * 32 * D;

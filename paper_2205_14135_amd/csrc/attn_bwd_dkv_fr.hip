@@ -62,14 +62,17 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr_kernel(const KArgs a) {
   // column each and leave the heavy ones alone; those were cut into segments by
   // sparse_plan_kernel and the remaining workgroups walk that segment list.
   const int n_col_groups = kXcds * a.chunk;
-  const bool list_mode = SPARSE && (int)blockIdx.x >= n_col_groups;
+  // (the list workgroups come first in the grid, a multiple of the XCD count of them, so that the
+  // long segments start with the launch instead of queueing behind every column)
+  const int n_list = SPARSE ? (int)gridDim.x - n_col_groups : 0;
+  const bool list_mode = SPARSE && (int)blockIdx.x < n_list;
   constexpr bool PAIRED = CAUSAL && !SPARSE;
   const int n_pair = (n_kt + 1) / 2;
   for (int round = 0;; ++round) {
   int item, skip_blocks = 0, take_blocks = 0x7fffffff;
   bool heavy = false, last_round = true;
   if (!list_mode) {
-    item = xcd_item(a.n_items, a.chunk);
+    item = xcd_item(a.n_items, a.chunk, (int)blockIdx.x - n_list);
     if (item < 0) return;
     if constexpr (SPARSE) {
       if (a.colcnt[item] > a.seglist[2]) return;
@@ -80,7 +83,7 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr_kernel(const KArgs a) {
       item = (item / n_pair) * n_kt + (round == 0 ? q : n_kt - 1 - q);
     }
   } else {
-    const int idx = ((int)blockIdx.x - n_col_groups) + round * ((int)gridDim.x - n_col_groups);
+    const int idx = (int)blockIdx.x + round * n_list;
     if (idx >= a.seglist[0]) return;
     const int e = a.seglist[kSegHeader + idx];
     item = e / kMaxSegs;
@@ -311,18 +314,13 @@ __global__ __launch_bounds__(NT, 2) void dkv_fr_kernel(const KArgs a) {
   }
 
   if (SPARSE && heavy) {
-    // one of several segments of this column: sum in fp32; sparse_finish_kernel converts
-    float* dst_v = a.dVacc + ((int64_t)bh * a.N + kj) * D;
-    float* dst_k = a.dKacc + ((int64_t)bh * a.N + kj) * D;
-    const float sv = DROPOUT ? a.keep_scale : 1.f;
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int col = 32 * db + 8 * (i >> 2) + 4 * g + (i & 3);
-        unsafeAtomicAdd(dst_v + col, dv[db][i] * sv);
-        unsafeAtomicAdd(dst_k + col, dk[db][i] * a.tau);
-      }
+    // one of several segments of this column: sum in fp32; sparse_finish_kernel converts.  The loop
+    // ended on a barrier: the two Q buffers stage the rows of wavefronts 0 and 1, the two dO buffers
+    // those of wavefronts 2 and 3 (32 x D floats each), first for dV, then for dK
+    float* stage = (float*)(wave < 2 ? Qs0 : Gs0) + (wave & 1) * 32 * D;
+    const int64_t acc_row0 = ((int64_t)bh * a.N + kw0) * D;
+    atomic_add_rows_coalesced<D>(stage, a.dVacc + acc_row0, dv, DROPOUT ? a.keep_scale : 1.f, D == 32 ? a.dvalid : D);
+    atomic_add_rows_coalesced<D>(stage, a.dKacc + acc_row0, dk, a.tau, D == 32 ? a.dvalid : D);
   } else {
     // the loop ends on a barrier (or never touched LDS): the tile buffers stage the output rows
     T* stage_v = Qs0 + wave * 32 * D;   // 4 wavefronts x 32 rows = the two Q buffers

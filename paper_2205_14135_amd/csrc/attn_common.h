@@ -405,8 +405,7 @@ __device__ __forceinline__ void softmax_tile_lane_query(const KArgs& a, f32x16 (
 
 // Work-item index for this workgroup: consecutive items share an XCD (workgroups are
 // dealt round-robin to the 8 XCDs, each with its own L2).  Returns -1 for padding groups.
-__device__ __forceinline__ int xcd_item(int n_items, int chunk) {
-  const int id = blockIdx.x;
+__device__ __forceinline__ int xcd_item(int n_items, int chunk, int id = (int)blockIdx.x) {
   const int item = (id % kXcds) * chunk + id / kXcds;
   return item < n_items && (id / kXcds) < chunk ? item : -1;
 }

@@ -227,4 +227,35 @@ __device__ __forceinline__ void store_rows_coalesced(T* stage, T* dst_row0, int6
   }
 }
 
+// The same accumulator tile added into an fp32 array (row stride D floats) with atomics, for
+// partial results that several workgroups sum: staged in fp32 (32 x D floats per wavefront) so that
+// one atomic instruction covers 64 consecutive floats of a row.  Atomics of device scope are
+// carried out beyond the XCD's L2, one request per 64-byte line: straight from the accumulator
+// layout (a lane holds four consecutive floats of its own row) an instruction touched 32 lines,
+// this way four.
+template <int D>
+__device__ __forceinline__ void atomic_add_rows_coalesced(float* stage, float* dst_row0, const f32x16 (&acc)[D / 32],
+                                                          float scale, int cols_valid = D) {
+  constexpr int C4 = D / 4;   // 16-byte chunks per row
+  const int lane = threadIdx.x & 63, r = lane & 31, g = lane >> 5;
+#pragma unroll
+  for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+    for (int i4 = 0; i4 < 4; ++i4) {
+      f32x4 v;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = acc[db][4 * i4 + e] * scale;
+      const int chunk = (8 * db + 2 * i4 + g) ^ (r & (C4 - 1));
+      *(f32x4*)(stage + r * D + 4 * chunk) = v;
+    }
+  __builtin_amdgcn_wave_barrier();   // same wavefront: LDS operations complete in program order
+#pragma unroll 4
+  for (int p = 0; p < D / 2; ++p) {
+    const int f = 64 * p + lane, row = f / D, col = f % D;
+    const float v = stage[row * D + 4 * ((col >> 2) ^ (row & (C4 - 1))) + (col & 3)];
+    if (col < cols_valid) unsafeAtomicAdd(dst_row0 + row * D + col, v);
+  }
+  __builtin_amdgcn_wave_barrier();
+}
+
 }  // namespace attn
