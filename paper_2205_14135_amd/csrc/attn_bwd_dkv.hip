@@ -365,32 +365,46 @@ __global__ __launch_bounds__(64 * kCountRowGroups) void sparse_count_kernel(cons
   }
   part[rg][c] = cnt;
   __syncthreads();
-  if (rg == 0 && kt < n_kt) {
+  if (rg == 0) {   // one wavefront: the column totals, then their sum as ONE atomic per workgroup
 #pragma unroll
     for (int g = 1; g < kCountRowGroups; ++g) cnt += part[g][c];
-    a.colcnt[bh * n_kt + kt] = cnt;
-    if (cnt > 0) atomicAdd(a.seglist + 1, cnt);
+    if (kt < n_kt) a.colcnt[bh * n_kt + kt] = cnt;
+    int sum = kt < n_kt ? cnt : 0;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) sum += __shfl_down(sum, off, 64);
+    if (c == 0 && sum > 0) atomicAdd(a.seglist + 1, sum);
   }
 }
 
 // Step 2: the heavy threshold, the segment list of the heavy columns and zeroed fp32
-// accumulators for them.  One 64-thread group per (bh, kt).
+// accumulators for them.  One 256-thread group per kPlanCols consecutive columns (bh, kt): most
+// columns are light and need one comparison, so a group per column would be launch overhead only.
+constexpr int kPlanCols = 16;
 template <int D>
-__global__ __launch_bounds__(64) void sparse_plan_kernel(const KArgs a) {
-  const int item = blockIdx.x;
+__global__ __launch_bounds__(256) void sparse_plan_kernel(const KArgs a) {
+  __shared__ int heavy_col[kPlanCols];
   const int n_kt = a.T;
-  const int bh = item / n_kt, kt = item % n_kt;
+  const int n_cols = a.B * a.H * n_kt;
+  const int first = blockIdx.x * kPlanCols;
   const int thr = max((int)kHeavyBlocks, a.seglist[1] / (2 * kComputeUnits));
-  if (item == 0 && threadIdx.x == 0) a.seglist[2] = thr;
-  const int cnt = a.colcnt[item];
-  if (cnt > thr) {
-    if (threadIdx.x == 0) {
+  if (blockIdx.x == 0 && threadIdx.x == 0) a.seglist[2] = thr;
+  if (threadIdx.x < kPlanCols) {
+    const int item = first + (int)threadIdx.x;
+    const int cnt = item < n_cols ? a.colcnt[item] : 0;
+    heavy_col[threadIdx.x] = cnt > thr;
+    if (cnt > thr) {
       const int nseg = min((int)kMaxSegs, (cnt + kSegBlocks - 1) / kSegBlocks);
       const int at = atomicAdd(a.seglist, nseg);
       for (int sgi = 0; sgi < nseg; ++sgi) a.seglist[kSegHeader + at + sgi] = item * kMaxSegs + sgi;
     }
+  }
+  __syncthreads();
+  for (int cidx = 0; cidx < kPlanCols; ++cidx) {
+    if (!heavy_col[cidx]) continue;
+    const int item = first + cidx;
+    const int bh = item / n_kt, kt = item % n_kt;
     const int64_t off = ((int64_t)bh * a.N + (int64_t)kt * 128) * D;
-    for (int i = threadIdx.x; i < 128 * D / 4; i += 64) {
+    for (int i = threadIdx.x; i < 128 * D / 4; i += 256) {
       const f32x4 z = {0.f, 0.f, 0.f, 0.f};
       *(f32x4*)(a.dKacc + off + 4 * i) = z;
       *(f32x4*)(a.dVacc + off + 4 * i) = z;
@@ -398,27 +412,33 @@ __global__ __launch_bounds__(64) void sparse_plan_kernel(const KArgs a) {
   }
 }
 
-// Block-sparse finish: dK, dV of the split columns, fp32 accumulators -> 16-bit outputs.
+// Block-sparse finish: dK, dV of the split columns, fp32 accumulators -> 16-bit outputs (same
+// grouping of columns as the plan kernel).
 template <typename T, int D>
 __global__ __launch_bounds__(256) void sparse_finish_kernel(const KArgs a) {
   typedef typename Vec<T>::x4 T4;
-  const int item = blockIdx.x;
-  if (a.colcnt[item] <= a.seglist[2]) return;
   const int n_kt = a.T;
-  const int bh = item / n_kt, kt = item % n_kt;
-  const int64_t head_off = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
-  const int64_t acc_off = ((int64_t)bh * a.N + (int64_t)kt * 128) * D;
-  for (int i = threadIdx.x; i < 128 * D / 4; i += 256) {
-    const int row = (4 * i) / D, colx = (4 * i) % D;
-    const f32x4 k4 = *(const f32x4*)(a.dKacc + acc_off + 4 * i);
-    const f32x4 v4 = *(const f32x4*)(a.dVacc + acc_off + 4 * i);
-    T4 ko, vo;
+  const int n_cols = a.B * a.H * n_kt;
+  const int thr = a.seglist[2];
+  for (int cidx = 0; cidx < kPlanCols; ++cidx) {
+    const int item = blockIdx.x * kPlanCols + cidx;
+    if (item >= n_cols) return;
+    if (a.colcnt[item] <= thr) continue;
+    const int bh = item / n_kt, kt = item % n_kt;
+    const int64_t head_off = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
+    const int64_t acc_off = ((int64_t)bh * a.N + (int64_t)kt * 128) * D;
+    for (int i = threadIdx.x; i < 128 * D / 4; i += 256) {
+      const int row = (4 * i) / D, colx = (4 * i) % D;
+      const f32x4 k4 = *(const f32x4*)(a.dKacc + acc_off + 4 * i);
+      const f32x4 v4 = *(const f32x4*)(a.dVacc + acc_off + 4 * i);
+      T4 ko, vo;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) { ko[e] = (T)k4[e]; vo[e] = (T)v4[e]; }
-    const int64_t o = head_off + (int64_t)(kt * 128 + row) * a.sn + colx;
-    if (D == 32 && colx >= a.dvalid) continue;   // head dimension 16: the tensors' rows end there
-    *(T4*)((T*)a.dK + o) = ko;
-    *(T4*)((T*)a.dV + o) = vo;
+      for (int e = 0; e < 4; ++e) { ko[e] = (T)k4[e]; vo[e] = (T)v4[e]; }
+      const int64_t o = head_off + (int64_t)(kt * 128 + row) * a.sn + colx;
+      if (D == 32 && colx >= a.dvalid) continue;   // head dimension 16: the tensors' rows end there
+      *(T4*)((T*)a.dK + o) = ko;
+      *(T4*)((T*)a.dV + o) = vo;
+    }
   }
 }
 
@@ -431,7 +451,7 @@ int launch_td(KArgs a, bool causal, bool dropout, bool sparse, hipStream_t s) {
   if (sparse) {
     a.causal = causal;
     hipLaunchKernelGGL(sparse_count_kernel, dim3(a.B * a.H * ((a.T + 63) / 64)), dim3(64 * kCountRowGroups), 0, s, a);
-    hipLaunchKernelGGL((sparse_plan_kernel<D>), dim3(cols), dim3(64), 0, s, a);
+    hipLaunchKernelGGL((sparse_plan_kernel<D>), dim3((cols + kPlanCols - 1) / kPlanCols), dim3(256), 0, s, a);
     const int e = (int)hipGetLastError();
     if (e != 0) return e;
   }
@@ -444,7 +464,7 @@ int launch_td(KArgs a, bool causal, bool dropout, bool sparse, hipStream_t s) {
     // d <= 64: the kernel in which one wavefront does all four products, same work assignment
     int e = launch_dkv_fr(a, std::is_same<T, __bf16>::value ? 1 : 0, D, causal, dropout, true, kListGroups, s);
     if (e == 0) {
-      hipLaunchKernelGGL((sparse_finish_kernel<T, D>), dim3(cols), dim3(256), 0, s, a);
+      hipLaunchKernelGGL((sparse_finish_kernel<T, D>), dim3((cols + kPlanCols - 1) / kPlanCols), dim3(256), 0, s, a);
       e = (int)hipGetLastError();
     }
     return e;
@@ -455,7 +475,7 @@ int launch_td(KArgs a, bool causal, bool dropout, bool sparse, hipStream_t s) {
     hipLaunchKernelGGL((dkv_rs_kernel<T, D, C, P, S>), grid, block, 0, s, a);     \
     int e = (int)hipGetLastError();                                               \
     if (e == 0 && S) {                                                            \
-      hipLaunchKernelGGL((sparse_finish_kernel<T, D>), dim3(cols), dim3(256), 0, s, a); \
+      hipLaunchKernelGGL((sparse_finish_kernel<T, D>), dim3((cols + kPlanCols - 1) / kPlanCols), dim3(256), 0, s, a); \
       e = (int)hipGetLastError();                                                 \
     }                                                                             \
     return e;                                                                     \
