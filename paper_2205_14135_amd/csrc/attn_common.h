@@ -167,10 +167,6 @@ __device__ __forceinline__ Keep4 keep4(uint32_t w, uint32_t carry2) {
   k.odd = __builtin_amdgcn_perm(0u, w, 0x0C030C01u) + carry2;   // (w >> 8) & 0x00FF00FF in one instruction
   return k;
 }
-// all ones if field f (0..3, a constant) of the word was kept, else zero
-__device__ __forceinline__ uint32_t keep_mask(const Keep4& k, int f) {
-  return (uint32_t)__builtin_amdgcn_sbfe((int)((f & 1) ? k.odd : k.even), 8 + 16 * (f >> 1), 1);
-}
 __device__ __forceinline__ float keep_or_zero(float x, uint32_t mask) {
   return __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, x) & mask);
 }
@@ -256,9 +252,10 @@ __device__ __forceinline__ KeepLQ keep_tile_lane_query(int k0, int qi, int bh, i
 // A call decides 16 consecutive keys of one query, i.e. the 16 lanes of one row of the wavefront
 // (same g, same r / 16), which all need the draws of the same 32 queries.  Lane u = r % 16 of a row
 // draws the two queries (qb = 0, 1; i4 = u / 4, e = u % 4) and packs their keep bits into one word,
-// bit 16 qb + key.  keep_words_lane_key() then hands every lane the words of all 16 lanes of its
-// row (a row broadcast through the LDS crossbar, no memory involved): w[i4][e] bit (r % 16) + 16 qb
-// is this lane's key for query (qb, i4, e).
+// bit 16 qb + key.  Every lane then needs the words of all 16 lanes of its row: word 4 i4 + e,
+// bit (r % 16) + 16 qb, is this lane's key for query (qb, i4, e).  Two ways to hand them round:
+// keep_words_lane_key() (row broadcasts through the LDS crossbar, no memory involved, a row group
+// of four words at a time) and keep_row_store() / keep_row_load*() (through an LDS slot).
 __device__ __forceinline__ uint32_t draw_keep_lane_key(int i0, int kj, int r, int g, int bh, uint32_t offset_lo,
                                                        uint32_t seed_lo, uint32_t seed_hi, uint32_t thr8) {
   const int u = r & 15;
@@ -277,20 +274,7 @@ template <int SRC> __device__ __forceinline__ uint32_t row16_broadcast(uint32_t 
   // ds_swizzle, bit mode within 32 lanes: source lane = (lane & 0x10) | SRC
   return (uint32_t)__builtin_amdgcn_ds_swizzle((int)x, 0x10 | (SRC << 5));
 }
-__device__ __forceinline__ KeepLK keep_words_lane_key(uint32_t mine) {
-  KeepLK k;
-  k.w[0][0] = row16_broadcast<0>(mine);   k.w[0][1] = row16_broadcast<1>(mine);
-  k.w[0][2] = row16_broadcast<2>(mine);   k.w[0][3] = row16_broadcast<3>(mine);
-  k.w[1][0] = row16_broadcast<4>(mine);   k.w[1][1] = row16_broadcast<5>(mine);
-  k.w[1][2] = row16_broadcast<6>(mine);   k.w[1][3] = row16_broadcast<7>(mine);
-  k.w[2][0] = row16_broadcast<8>(mine);   k.w[2][1] = row16_broadcast<9>(mine);
-  k.w[2][2] = row16_broadcast<10>(mine);  k.w[2][3] = row16_broadcast<11>(mine);
-  k.w[3][0] = row16_broadcast<12>(mine);  k.w[3][1] = row16_broadcast<13>(mine);
-  k.w[3][2] = row16_broadcast<14>(mine);  k.w[3][3] = row16_broadcast<15>(mine);
-  return k;
-}
-// The same exchange through LDS, for kernels that fetch a row group where they use it (they cannot
-// hold all sixteen words): every lane stores its packed word into its wavefront's 64-word slot, and
+// The exchange through LDS: every lane stores its packed word into its wavefront's 64-word slot, and
 // the four words of row group i4 of a lane's 16-lane row are one 16-byte read (all lanes of the row
 // read the same address).  No barrier: one wavefront's LDS instructions execute in order.
 struct KeepLK4 { uint32_t w[4]; };
@@ -316,8 +300,8 @@ __device__ __forceinline__ KeepLK keep_row_load_all(const uint32_t* slot64) {
 __device__ __forceinline__ float dropped_dp_minus_d(float dp, float keep_scale, uint32_t mask, float neg_d) {
   return __builtin_fmaf(dp, __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, keep_scale) & mask), neg_d);
 }
-// The four words of row group i4 only (i4 a constant after unrolling), for kernels that cannot
-// afford to hold all sixteen: they fetch a row group where they use it.
+// The row broadcasts: the four words of row group i4 (a constant after unrolling), fetched where
+// they are used by kernels that cannot afford to hold all sixteen.
 __device__ __forceinline__ KeepLK4 keep_words_lane_key(uint32_t mine, int i4) {
   KeepLK4 k;
   switch (i4) {
