@@ -89,8 +89,8 @@ def _run(B, H, N, d, dtype, *, causal=False, p=0.0, lengths=None, o_fp32=False, 
             bounds = hp.vanishing_gradient_bounds(
                 t["Q"][b, h], t["K"][b, h], t["V"][b, h], t["dO"][b, h], Oo, tau,
                 min(N if klen is None else klen, N), o_round=None if o_fp32 else dtype,
-                keep_scale=1.0 / (1.0 - orc.dropout_effective_p(p)) if p > 0 else 1.0) \
-                if min(N if klen is None else klen, N) <= 1 else None
+                keep_scale=1.0 / (1.0 - orc.dropout_effective_p(p)) if p > 0 else 1.0, keep=keep, causal=causal) \
+                if min(N if klen is None else klen, N) <= 1 or (keep is not None and not keep.any()) else None
             for name, got, want in zip(("dQ", "dK", "dV"), grads, ref):
                 assert np.isfinite(got[b, h]).all(), name
                 # at most one visible key: the exact dQ, dK vanish, the round-off is bounded instead
