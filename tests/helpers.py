@@ -42,40 +42,40 @@ def round_to(x: np.ndarray, dtype: str) -> np.ndarray:
     return torch.from_numpy(np.ascontiguousarray(x, dtype=np.float64)).to(tdt).double().numpy()
 
 
-def vanishing_gradient_bounds(Qh, Kh, Vh, dOh, Oo, tau, n_keys, *, o_round=None, keep_scale=1.0, keep=None, causal=False):
+def vanishing_gradient_bounds(Qh, Kh, Vh, dOh, Oo, tau, alive, *, o_round=None, keep_scale=1.0):
     """Element-wise bounds on |dQ|, |dK|, |dV| of one head whose exact gradient is zero.
 
-    With at most one visible key (keys [0, n_keys), n_keys <= 1) dS = P (dP - D) vanishes because the
-    two length-d dot products dP_ij = dO_i . v_j (scaled by keep_scale under dropout) and
-    D_i = dO_i . O_i are equal; a kernel computes both in fp32 (unit roundoff u = 2^-24) from exact
-    products of 16-bit values, so by the standard bound for a recursive sum each is off by at most
-    d u sum_k |dO_ik v_jk| (taken twice over for the keep_scale product and a different summation
-    order).  When O was stored in a 16-bit type (o_round), D also carries sum_k |dO_ik| |O_ik - round(O_ik)|.
-    P <= 1 (1.001 covers its own rounding), so |dS_ij| <= e_ij and the bounds are
-    |dQ_i| <= tau sum_j e_ij |k_j| and |dK_j| <= tau sum_i e_ij |q_i|.  Without any visible key every
-    gradient, dV included, must be exactly zero; with one, dV does not vanish (None).  The same holds
-    when dropout (keep: the head's keep mask) removed every visible entry: O = 0, hence D = 0 and
-    dS = P (0 - 0): exact zeros."""
+    alive: boolean [N, N], the entries that are visible (all masks) and, under dropout, kept.
+    Where every row has at most one alive key, dS = P (dP - D) vanishes because the two length-d dot
+    products dP_ij = dO_i . v_j (scaled by keep_scale under dropout) and D_i = dO_i . O_i are equal;
+    a kernel computes both in fp32 (unit roundoff u = 2^-24) from exact products of 16-bit values, so
+    by the standard bound for a recursive sum each is off by at most d u sum_k |dO_ik v_jk| (taken
+    twice over for the keep_scale product and a different summation order).  When O was stored in a
+    16-bit type (o_round), D also carries sum_k |dO_ik| |O_ik - round(O_ik)|.  P <= 1 (1.001 covers its
+    own rounding), so |dS_ij| <= e_ij on the alive entries and the bounds are |dQ_i| <= tau sum_j e_ij
+    |k_j| and |dK_j| <= tau sum_i e_ij |q_i|.  Without any alive entry every gradient, dV included,
+    must be exactly zero (O = 0, hence D = 0 and dS = P (0 - 0)); with one, dV does not vanish (None)."""
     N, d = Qh.shape
     u = 2.0 ** -24
     aQ, aK, aV, adO = (np.abs(x.astype(np.float64)) for x in (Qh, Kh, Vh, dOh))
-    bQ, bK, bV = np.zeros((N, d)), np.zeros((N, d)), np.zeros((N, d))
-    if keep is not None:   # entries that are visible (key within the length, not above the diagonal) and kept
-        # (tokens at or beyond a key length are padding as queries too: n_keys bounds both axes)
-        alive = np.asarray(keep, dtype=bool)[:n_keys, :n_keys]
-        if causal:
-            alive = alive & np.tril(np.ones((n_keys, n_keys), dtype=bool))
-    if n_keys == 0 or (keep is not None and not alive.any()):
-        return bQ, bK, bV
-    e = 4.0 * d * u * keep_scale * (adO @ aV[:n_keys].T)                    # [N, n_keys]
+    alive = np.asarray(alive, dtype=bool)
+    if not alive.any():
+        return np.zeros((N, d)), np.zeros((N, d)), np.zeros((N, d))
+    e = 4.0 * d * u * keep_scale * (adO @ aV.T)                             # [N, N]
     if o_round is not None:
         e = e + (adO * np.abs(Oo - round_to(Oo, o_round))).sum(axis=1, keepdims=True)
-    e *= 1.001
-    bQ = tau * (e @ aK[:n_keys])
+    e = 1.001 * e * alive
+    bQ = tau * (e @ aK)
     # dK_j sums one term per query row; the rows' round-offs are independent, so beyond a few rows the
     # sum of absolute terms is replaced by six times their root-sum-square
-    bK[:n_keys] = tau * np.minimum(e.T @ aQ, 6.0 * np.sqrt((e.T ** 2) @ (aQ ** 2)))
+    bK = tau * np.minimum(e.T @ aQ, 6.0 * np.sqrt((e.T ** 2) @ (aQ ** 2)))
     return bQ, bK, None
+
+
+def alive_entries(N, *, causal=False, block_mask=None, key_length=None, keep=None):
+    """Visible entries of a head (causal, block and key-padding masks) that dropout kept."""
+    vis = orc.visible_mask(N, causal=causal, block_mask=block_mask, key_length=key_length)
+    return vis if keep is None else vis & np.asarray(keep, dtype=bool)
 
 
 def check_vanishing(name, got, want_norm, bounds):
@@ -177,9 +177,9 @@ def check_backward(t, dev, dtype, tau, *, causal=False, p=0.0, seed=0, offset=0,
                                              p_drop=p, keep=keep, block_mask=bm_h, key_length=klen)
                     bounds = vanishing_gradient_bounds(
                         t["Q"][b, h], t["K"][b, h], t["V"][b, h], t["dO"][b, h], Oo, tau,
-                        min(N if klen is None else klen, N), o_round=None if o_fp32 else dtype,
-                        keep_scale=1.0 / (1.0 - orc.dropout_effective_p(p)) if p > 0 else 1.0, keep=keep,
-                        causal=causal)
+                        alive_entries(N, causal=causal, block_mask=bm_h, key_length=klen, keep=keep),
+                        o_round=None if o_fp32 else dtype,
+                        keep_scale=1.0 / (1.0 - orc.dropout_effective_p(p)) if p > 0 else 1.0)
                 check_vanishing(name, got[b, h], norm, bounds)
                 continue
             res[name] = max(res[name], rel_l2(got[b, h], want))

@@ -52,3 +52,40 @@ def test_random_configurations(stream):
     finally:
         binding.attn_debug_set_variant(fwd="auto", dkv="auto")
     assert fallbacks <= 2
+
+
+@pytest.mark.parametrize("stream", [21, 22])
+def test_random_block_sparse_configurations(stream):
+    """The block-sparse entry points on random block masks: shared and per-head masks, densities from
+    0.1 to 0.9, empty masks and empty row blocks, a column that keeps everything (split over several
+    workgroups), with the causal mask, dropout and key lengths."""
+    rng = np.random.default_rng(stream)
+    try:
+        for case in range(30):
+            d = int(rng.choice([16, 32, 64, 128]))
+            dtype = str(rng.choice(["bf16", "fp16"]))
+            B, H, T = int(rng.integers(1, 3)), int(rng.integers(1, 4)), int(rng.choice([1, 2, 3, 5, 8, 40]))
+            N = 128 * T
+            causal = bool(rng.integers(0, 2))
+            p = float(rng.choice([0.0, 0.0, 0.1, 0.3]))
+            per_head = bool(rng.integers(0, 2))
+            density = float(rng.choice([0.1, 0.4, 0.9]))
+            bm = (rng.random((H, T, T) if per_head else (T, T)) < density).astype(np.uint8)
+            if rng.integers(0, 2):
+                bm[..., 0] = 1                                   # a heavy column
+            if rng.integers(0, 3) == 0 and T > 1:
+                bm[..., int(rng.integers(0, T)), :] = 0          # a row block that sees nothing
+            lengths = [int(rng.integers(0, N + 1)) for _ in range(B)] if rng.integers(0, 4) == 0 else None
+            dkvv = str(rng.choice(["auto", "rs"]))
+            seed, offset = int(rng.integers(0, 2 ** 62)), int(rng.integers(0, 2 ** 33))
+            print(f"stream {stream} case {case}: B{B} H{H} T{T} d{d} {dtype} causal={causal} p={p} per_head={per_head} "
+                  f"kept={int(bm.sum())} len={lengths} dkv={dkvv}", flush=True)
+            binding.attn_debug_set_variant(dkv=dkvv)
+            t, dev = hp.make_case(B, H, N, d, dtype, 9000 + 100 * stream + case)
+            heads = [(int(rng.integers(0, B)), int(rng.integers(0, H)))] if T >= 40 else None
+            kw = dict(causal=causal, p=p, seed=seed, offset=offset, key_lengths=lengths, block_mask=bm, heads=heads)
+            tau = 1.0 / math.sqrt(d)
+            hp.assert_forward_ok(hp.check_forward(t, dev, dtype, tau, **kw))
+            hp.assert_backward_ok(hp.check_backward(t, dev, dtype, tau, **kw))
+    finally:
+        binding.attn_debug_set_variant(fwd="auto", dkv="auto")

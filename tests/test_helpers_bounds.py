@@ -41,7 +41,8 @@ def test_bound_holds_for_a_float32_kernel_and_catches_a_wrong_row_term(dtype, d,
     scale = 1.0 / (1.0 - orc.dropout_effective_p(p)) if p > 0 else 1.0
     Q, K, V, dO = (t[n][0, 0] for n in ("Q", "K", "V", "dO"))
     Oo = np.tile(V[0].astype(np.float64) * scale, (N, 1))          # exact output of every row (all keys kept)
-    bQ, bK, bV = hp.vanishing_gradient_bounds(Q, K, V, dO, Oo, tau, 1, o_round=dtype, keep_scale=scale)
+    alive = hp.alive_entries(N, key_length=None) & (np.arange(N)[None, :] == 0)      # key 0 only
+    bQ, bK, bV = hp.vanishing_gradient_bounds(Q, K, V, dO, Oo, tau, alive, o_round=dtype, keep_scale=scale)
     assert bV is None                                              # dV does not vanish with a visible key
     dQ, dK = _emulate_single_key(t, tau, dtype, scale)
     assert (np.abs(dQ) <= bQ).all() and (np.abs(dK) <= bK).all()
@@ -59,7 +60,7 @@ def test_bound_holds_for_a_float32_kernel_and_catches_a_wrong_row_term(dtype, d,
 def test_no_visible_key_means_exact_zeros():
     t = inputs.gaussian_tensors(1, 1, 8, 32, "bf16", 7)
     Q, K, V, dO = (t[n][0, 0] for n in ("Q", "K", "V", "dO"))
-    bounds = hp.vanishing_gradient_bounds(Q, K, V, dO, np.zeros((8, 32)), 0.2, 0)
+    bounds = hp.vanishing_gradient_bounds(Q, K, V, dO, np.zeros((8, 32)), 0.2, hp.alive_entries(8, key_length=0))
     assert all((b == 0).all() for b in bounds)
     assert hp.check_vanishing("dV", np.zeros((8, 32)), 0.0, bounds)
     with pytest.raises(AssertionError):
